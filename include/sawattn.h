@@ -1,0 +1,113 @@
+/*
+ * sawattn -- FlashAttention forward with Sawtooth Wavefront Reordering for AMD MI355X (gfx950).
+ *
+ * C ABI of libsawattn.so.  Plain pointers and sizes only; every pointer named "device" must be a
+ * HIP device pointer on the current device, every pointer named "host" an ordinary host pointer.
+ * No function here throws, aborts, allocates device memory or synchronises the device, unless its
+ * comment says otherwise.  All functions return SAWATTN_OK or an error code; the text of the last
+ * error on the calling thread is available from sawattn_last_error().
+ */
+#ifndef SAWATTN_H
+#define SAWATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SAWATTN_OK = 0,
+    SAWATTN_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, non-positive size, bad enum, overflow */
+    SAWATTN_ERR_UNSUPPORTED = 2,   /* head dimension other than 64 or 128 */
+    SAWATTN_ERR_RUNTIME = 3        /* the HIP runtime refused the launch */
+};
+
+/* Order in which a workgroup walks the K/V tiles of one query tile (paper Sec. 4, Alg. 4). */
+enum {
+    SAWATTN_SCAN_CYCLIC = 0,       /* always ascending */
+    SAWATTN_SCAN_SAWTOOTH = 1      /* ascending on even rounds, descending on odd rounds */
+};
+
+enum {
+    SAWATTN_F16 = 0,               /* IEEE binary16 */
+    SAWATTN_BF16 = 1,              /* bfloat16 */
+    SAWATTN_F32 = 2                /* IEEE binary32; allowed for the output only */
+};
+
+/*
+ * attn_fwd -- O = softmax(Q K^T * scale) V  (paper Sec. 2.2, Eq. 1), computed tile by tile with an
+ * online softmax (Alg. 1) by persistent workgroups (Alg. 2) that scan K/V in `scan_order` (Alg. 4).
+ *
+ *   Q, K, V  device, read only.  Contiguous [B, H, N, d], d fastest, element type `in_dtype`
+ *            (SAWATTN_F16 or SAWATTN_BF16), 16-byte aligned.  Query and key sequences both have
+ *            length N; each (batch, head) pair is an independent attention problem.
+ *   O        device, written.  Contiguous [B, H, N, d], element type `o_dtype` (F16, BF16 or F32),
+ *            16-byte aligned.  Every element is overwritten.
+ *   B, H, N  >= 1.   d must be 64 or 128.   B*H*N*d must be below 2^40 and B*H*ceil(N/128) below 2^31.
+ *   scale    any finite float (1/sqrt(d) in the paper); the scores are multiplied by it.
+ *   causal   0: every key is visible;  non-zero: key j is visible to query i iff j <= i.
+ *   scan_order  SAWATTN_SCAN_CYCLIC or SAWATTN_SCAN_SAWTOOTH.  Both give the same O up to the
+ *            rounding of a different fp32 summation order.
+ *   hip_stream  a hipStream_t (NULL = the default stream).  The kernel is enqueued there and the call
+ *            returns without waiting; the caller keeps all buffers alive until the stream has drained.
+ *
+ * Arithmetic: 16-bit inputs are multiplied exactly and accumulated in fp32 on the matrix cores; the
+ * running maximum, the running sum and the output accumulator are fp32; the probabilities are
+ * rounded to binary16 before the second contraction (for bf16 inputs V is converted to binary16 on
+ * the way into LDS, which is exact for |v| in [2^-14, 65504] -- larger bf16 values of V are not
+ * supported).  The caller owns every buffer; the library keeps no state besides the error text.
+ *
+ * Errors: INVALID_ARG / UNSUPPORTED as listed above (nothing is launched); RUNTIME if the launch
+ * fails.  Safe to call from several host threads.
+ */
+int attn_fwd(const void* Q, const void* K, const void* V, void* O,
+             int B, int H, int N, int d, float scale, int causal, int scan_order,
+             int in_dtype, int o_dtype, void* hip_stream);
+
+/* Launch geometry chosen for a problem; filled by attn_fwd_launch_info (host memory). */
+typedef struct sawattn_launch_info {
+    int tile_q;            /* query rows per workgroup tile */
+    int tile_kv;           /* key/value rows per streamed tile */
+    int block_threads;     /* threads per workgroup (64-wide wavefronts) */
+    int grid;              /* persistent workgroups launched, a multiple of `domains` */
+    int lds_bytes;         /* dynamic LDS per workgroup */
+    int domains;           /* cache domains (XCDs, one L2 each) the schedule is built for */
+    int slots;             /* workgroups per domain = grid / domains */
+    int parts_per_head;    /* domains that share one head's query tiles (1 when B*H % 8 == 0) */
+    int q_tiles_per_head;  /* ceil(N / tile_q) */
+    int max_local_tiles;   /* most query tiles any one workgroup processes */
+} sawattn_launch_info;
+
+/*
+ * attn_fwd_launch_info -- report the geometry attn_fwd would use (paper Sec. 2.2, Alg. 2: grid size
+ * and work decode).  `out` is host memory.  Validates B, H, N, d like attn_fwd.  Launches nothing.
+ */
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, sawattn_launch_info* out);
+
+/*
+ * attn_fwd_trace -- attn_fwd, and in addition every workgroup records which query tile it took at
+ * each of its local iterations and in which direction it walked the K/V tiles (paper Sec. 2.2
+ * Alg. 2 work decode, Sec. 4 Alg. 4 scan direction), so that the schedule can be checked.
+ *
+ *   trace        device, written: int32 [grid][max_local_tiles][4] = (b*H + h, query tile index,
+ *                first K/V tile visited, last K/V tile visited); grid and max_local_tiles from
+ *                attn_fwd_launch_info.  Unused records are left untouched.
+ *   trace_count  device, written: int32 [grid], the number of records each workgroup wrote.
+ * All other arguments, errors and stream behaviour as attn_fwd.
+ */
+int attn_fwd_trace(const void* Q, const void* K, const void* V, void* O,
+                   int B, int H, int N, int d, float scale, int causal, int scan_order,
+                   int in_dtype, int o_dtype, void* hip_stream,
+                   int32_t* trace, int32_t* trace_count);
+
+/* Text of the last error raised on the calling thread ("" if none).  Static storage, never NULL. */
+const char* sawattn_last_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int sawattn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAWATTN_H */

@@ -1,0 +1,126 @@
+"""ctypes binding of libsawattn.so: argument marshalling only, same names as the C ABI.
+
+Every step of the attention forward runs inside the HIP library.  There is no fallback: if the
+library has not been built, loading raises.  PyTorch is used for device memory and streams.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from .build import LIB_PATH
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_RUNTIME = 0, 1, 2, 3
+SCAN_CYCLIC, SCAN_SAWTOOTH = 0, 1
+F16, BF16, F32 = 0, 1, 2
+
+_DTYPE_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
+_SCAN_CODE = {"cyclic": SCAN_CYCLIC, "sawtooth": SCAN_SAWTOOTH, SCAN_CYCLIC: SCAN_CYCLIC,
+              SCAN_SAWTOOTH: SCAN_SAWTOOTH}
+
+
+class LaunchInfo(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in (
+        "tile_q", "tile_kv", "block_threads", "grid", "lds_bytes", "domains", "slots",
+        "parts_per_head", "q_tiles_per_head", "max_local_tiles")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class SawattnError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"sawattn error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsawattn.so (built by paper_2601_16032_amd.build.build()); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is not built; run `python -m paper_2601_16032_amd.build` "
+                "(or __graft_entry__.build()) first -- there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        L.attn_fwd.restype = ci
+        L.attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, ci, ci, ci, vp]
+        L.attn_fwd_trace.restype = ci
+        L.attn_fwd_trace.argtypes = L.attn_fwd.argtypes + [vp, vp]
+        L.attn_fwd_launch_info.restype = ci
+        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(LaunchInfo)]
+        L.sawattn_last_error.restype = ctypes.c_char_p
+        L.sawattn_last_error.argtypes = []
+        L.sawattn_version.restype = ci
+        L.sawattn_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def sawattn_last_error() -> str:
+    return lib().sawattn_last_error().decode()
+
+
+def sawattn_version() -> int:
+    return int(lib().sawattn_version())
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise SawattnError(rc, sawattn_last_error())
+
+
+def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False) -> dict:
+    info = LaunchInfo()
+    _check(lib().attn_fwd_launch_info(B, H, N, d, int(bool(causal)), ctypes.byref(info)))
+    return info.as_dict()
+
+
+def _marshal(Q, K, V, O, o_dtype):
+    for name, t in (("Q", Q), ("K", K), ("V", V)):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous [B, H, N, d] device tensor")
+    if not (Q.shape == K.shape == V.shape) or not (Q.dtype == K.dtype == V.dtype):
+        raise ValueError("Q, K, V must share shape and dtype")
+    if Q.dtype not in (torch.float16, torch.bfloat16):
+        raise ValueError("inputs must be float16 or bfloat16")
+    if O is None:
+        O = torch.empty(Q.shape, dtype=o_dtype or Q.dtype, device=Q.device)
+    elif not O.is_cuda or not O.is_contiguous() or O.shape != Q.shape or O.dtype not in _DTYPE_CODE:
+        raise ValueError("O must be a contiguous device tensor shaped like Q (f16, bf16 or f32)")
+    return O
+
+
+def attn_fwd(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order="sawtooth",
+             o_dtype=None, stream=None):
+    """O = softmax(Q K^T * scale) V on the current (or given) stream; returns O without waiting."""
+    O = _marshal(Q, K, V, O, o_dtype)
+    B, H, N, d = Q.shape
+    st = stream if stream is not None else torch.cuda.current_stream(Q.device)
+    _check(lib().attn_fwd(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                          float(scale), int(bool(causal)), _SCAN_CODE[scan_order],
+                          _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream))
+    return O
+
+
+def attn_fwd_trace(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order="sawtooth",
+                   o_dtype=None, stream=None):
+    """attn_fwd plus the schedule record; returns (O, trace[grid, max_local, 4], count[grid])."""
+    O = _marshal(Q, K, V, O, o_dtype)
+    B, H, N, d = Q.shape
+    info = attn_fwd_launch_info(B, H, N, d, causal)
+    trace = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32,
+                       device=Q.device)
+    count = torch.zeros((info["grid"],), dtype=torch.int32, device=Q.device)
+    st = stream if stream is not None else torch.cuda.current_stream(Q.device)
+    _check(lib().attn_fwd_trace(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                float(scale), int(bool(causal)), _SCAN_CODE[scan_order],
+                                _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream,
+                                trace.data_ptr(), count.data_ptr()))
+    return O, trace, count

@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on the same
+seeded inputs.  Tolerance: max-abs 2e-3 and relative-L2 1e-3 (tests/util.py)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_16032_amd import workloads
+from tests.util import assert_close, errors
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sa():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2601_16032_amd import binding
+    binding.lib()
+    return binding
+
+
+def run_gpu(sa, Q, K, V, scale, causal, order, o_dtype=None):
+    O = sa.attn_fwd(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order,
+                    o_dtype=o_dtype)
+    torch.cuda.synchronize()
+    return O.double().cpu().numpy()
+
+
+ORDERS = ["cyclic", "sawtooth"]
+
+
+# ------------------------------------------------------------------ small workloads, every element
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_small_workloads_all_elements(sa, oracle, cfg, order):
+    w = workloads.WORKLOADS[cfg]
+    Q, K, V = workloads.make_qkv(w)
+    want = oracle.attention(Q, K, V, w.scale, causal=w.causal)
+    got = run_gpu(sa, Q, K, V, w.scale, w.causal, order)
+    print(w.name, order, assert_close(got, want, f"{w.name} {order}"))
+    got32 = run_gpu(sa, Q, K, V, w.scale, w.causal, order, o_dtype=torch.float32)
+    print(w.name, order, "f32 out", assert_close(got32, want, f"{w.name} {order} f32"))
+
+
+# ------------------------------------------------------------------ ragged and tiny shapes
+RAGGED = [1, 2, 5, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 200, 257, 333, 640, 1000]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("d", [64, 128])
+def test_ragged_lengths(sa, oracle, d, dtype, causal):
+    for k, N in enumerate(RAGGED):
+        B, H = (1, 1) if k % 3 == 0 else ((2, 3) if k % 3 == 1 else (1, 8))
+        Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=1000 + N)
+        scale = 1.0 / math.sqrt(d)
+        want = oracle.attention(Q, K, V, scale, causal=causal)
+        for order in ORDERS:
+            got = run_gpu(sa, Q, K, V, scale, causal, order, o_dtype=torch.float32)
+            assert_close(got, want, f"N={N} d={d} {dtype} causal={causal} B={B} H={H} {order}")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_many_rounds_and_heads(sa, oracle, causal):
+    """More query tiles than resident workgroups of a domain (several rounds, both directions) and
+    more heads than domains (several chunks per domain)."""
+    Q, K, V = workloads.make_random(1, 8, 128 * 70, 64, "f16", seed=77)   # 70 tiles per head: 2 rounds
+    rows = list(range(0, 128 * 70, 131)) + [128 * 70 - 1]
+    want = oracle.attention(Q, K, V, 0.125, causal=causal, rows=rows)
+    for order in ORDERS:
+        got = run_gpu(sa, Q, K, V, 0.125, causal, order, o_dtype=torch.float32)[:, :, rows]
+        assert_close(got, want, f"70 tiles causal={causal} {order}")
+    Q, K, V = workloads.make_random(3, 7, 300, 128, "bf16", seed=78)      # 21 heads, parts = 8
+    want = oracle.attention(Q, K, V, 0.09, causal=causal)
+    for order in ORDERS:
+        got = run_gpu(sa, Q, K, V, 0.09, causal, order, o_dtype=torch.float32)
+        assert_close(got, want, f"21 heads causal={causal} {order}")
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_scale_sign_and_zero(sa, oracle):
+    Q, K, V = workloads.make_random(1, 2, 300, 64, "f16", seed=5)
+    for scale in (-0.125, 0.0, 0.5, 1e-3):
+        for causal in (False, True):
+            want = oracle.attention(Q, K, V, scale, causal=causal)
+            got = run_gpu(sa, Q, K, V, scale, causal, "sawtooth", o_dtype=torch.float32)
+            assert_close(got, want, f"scale={scale} causal={causal}")
+
+
+def test_identical_keys_uniform_attention(sa, oracle):
+    Q, K, V = workloads.make_random(1, 2, 500, 128, "f16", seed=6)
+    K = K[:, :, :1].expand_as(K).contiguous()
+    for causal in (False, True):
+        want = oracle.attention(Q, K, V, 0.1, causal=causal)
+        got = run_gpu(sa, Q, K, V, 0.1, causal, "sawtooth", o_dtype=torch.float32)
+        assert_close(got, want, f"identical keys causal={causal}")
+
+
+def test_peaked_rows_one_hot(sa, oracle):
+    """Each query matches exactly one key with a large score: P is one-hot to fp16 precision."""
+    N, d = 384, 64
+    g = torch.Generator("cpu").manual_seed(7)
+    perm = torch.randperm(N, generator=g)
+    K = torch.zeros(1, 1, N, d)
+    K[0, 0, torch.arange(N), torch.arange(N) % d] = 1.0
+    K[0, 0, :, :] += 0.01 * torch.randn(N, d, generator=g)
+    Q = 40.0 * K[:, :, perm]
+    V = torch.randn(1, 1, N, d, generator=g)
+    Q, K, V = Q.half(), K.half(), V.half()
+    want = oracle.attention(Q, K, V, 1.0)
+    for order in ORDERS:
+        got = run_gpu(sa, Q, K, V, 1.0, False, order, o_dtype=torch.float32)
+        assert_close(got, want, f"peaked {order}")
+
+
+def test_large_common_shift(sa, oracle):
+    """A large offset shared by all keys shifts every score of a row by the same amount."""
+    Q, K, V = workloads.make_random(1, 1, 256, 64, "bf16", seed=8)
+    K = (K.float() + 3.0).bfloat16()
+    want = oracle.attention(Q, K, V, 0.125)
+    got = run_gpu(sa, Q, K, V, 0.125, False, "sawtooth", o_dtype=torch.float32)
+    assert_close(got, want, "shifted keys")
+
+
+@pytest.mark.parametrize("o_dtype", [torch.float16, torch.bfloat16, torch.float32])
+def test_output_dtypes_round_the_same_accumulator(sa, o_dtype):
+    Q, K, V = workloads.make_random(1, 2, 300, 128, "bf16", seed=9, device="cuda")
+    ref = sa.attn_fwd(Q, K, V, scale=0.1, causal=True, scan_order="cyclic", o_dtype=torch.float32)
+    out = sa.attn_fwd(Q, K, V, scale=0.1, causal=True, scan_order="cyclic", o_dtype=o_dtype)
+    torch.cuda.synchronize()
+    assert out.dtype == o_dtype
+    assert torch.equal(out, ref.to(o_dtype))   # same kernel, same order: only the final rounding differs
+
+
+# ------------------------------------------------------------------ full-size workloads, sampled rows
+def sample_rows(N, seed, n=48):
+    g = np.random.default_rng(seed)
+    fixed = [0, 1, 63, 64, 127, 128, N // 2 - 1, N // 2, N - 129, N - 128, N - 1]
+    return sorted(set(fixed) | set(int(x) for x in g.integers(0, N, size=n)))
+
+
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_size_workloads_sampled_rows(sa, oracle, cfg):
+    w = workloads.WORKLOADS[cfg]
+    print("generating", w.name, flush=True)
+    Q, K, V = workloads.make_qkv(w)
+    Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+    o_dtype = torch.float32 if w.dtype == "bf16" else torch.float16
+    outs = {}
+    for order in ORDERS:
+        print("launch", w.name, order, flush=True)
+        outs[order] = sa.attn_fwd(Qd, Kd, Vd, scale=w.scale, causal=w.causal, scan_order=order,
+                                  o_dtype=o_dtype)
+        torch.cuda.synchronize()
+    g = np.random.default_rng(100 + cfg)
+    heads = {(0, 0), (w.B - 1, w.H - 1), (0, min(8, w.H - 1)), (w.B - 1, 7 % w.H)}
+    while len(heads) < 6:
+        heads.add((int(g.integers(0, w.B)), int(g.integers(0, w.H))))
+    rows = sample_rows(w.N, 200 + cfg)
+    for (b, h) in sorted(heads):
+        want = oracle.attention(Q[b:b + 1, h:h + 1], K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1],
+                                w.scale, causal=w.causal, rows=rows)[0, 0]
+        for order in ORDERS:
+            got = outs[order][b, h][rows].double().cpu().numpy()
+            e = assert_close(got, want, f"{w.name} head ({b},{h}) {order}")
+            print(w.name, (b, h), order, "max-abs %.2e rel-L2 %.2e" % e, flush=True)
+    # the two scan orders agree with each other everywhere (not only on the sampled rows)
+    a, c = outs["cyclic"], outs["sawtooth"]
+    diff = (a.float() - c.float())
+    assert torch.isfinite(a.float()).all() and torch.isfinite(c.float()).all()
+    max_abs = diff.abs().max().item()
+    rel = (diff.double().pow(2).sum().sqrt() / a.double().pow(2).sum().sqrt()).item()
+    print(w.name, "cyclic vs sawtooth: max-abs %.2e rel-L2 %.2e" % (max_abs, rel), flush=True)
+    assert max_abs <= 2e-3 and rel <= 1e-3
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_scan_orders_agree_small(sa, cfg):
+    w = workloads.WORKLOADS[cfg]
+    Q, K, V = workloads.make_qkv(w, device="cuda")
+    a = sa.attn_fwd(Q, K, V, scale=w.scale, causal=w.causal, scan_order="cyclic", o_dtype=torch.float32)
+    b = sa.attn_fwd(Q, K, V, scale=w.scale, causal=w.causal, scan_order="sawtooth", o_dtype=torch.float32)
+    torch.cuda.synchronize()
+    e = errors(b.cpu().numpy(), a.cpu().numpy())
+    assert e[0] <= 2e-3 and e[1] <= 1e-3
