@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the attention forward hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 4] [--scan-order sawtooth]
+
+A "step" is one attn_fwd call (work decode, scan-direction choice, Q load, K/V streaming, both
+contractions, online softmax, epilogue) over one batch of the seeded synthetic workload, inputs
+resident in HBM.  Prints ONE JSON line: whole-job TFLOP/s of the sawtooth order (4*B*H*N^2*d flops,
+halved under a causal mask), the MFMA roofline of the kernel measured live with events on the
+launch stream, the cyclic order timed the same way, and the fp64 CPU oracle timed on a bounded
+sample of the same workload (reported baseline only).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS_16BIT = 2500.0   # MI355X dense fp16/bf16 matrix peak
+
+# HBM-side bytes per launch, from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this
+# script (summaries and commands under profiles/), scaled by the reading of the same counter for a
+# plain copy of known size.  Keyed by (workload, scan order); absent = not measured.
+MEASURED_TRAFFIC_BYTES: dict = {}
+# TCC (L2) miss requests per launch from `rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum`.
+MEASURED_TCC_MISS: dict = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=4, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--scan-order", default="both", choices=["both", "sawtooth", "cyclic"],
+                    help="'both' times sawtooth (the headline) and cyclic; a single order is for profiling")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference reading for FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--evict", action="store_true",
+                    help="overwrite a 1 GiB scratch buffer before every step so each launch starts cache-cold")
+    return ap.parse_args()
+
+
+def time_order(sa, torch, Q, K, V, O, w, order, steps, warmup, evict_buf=None):
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        if evict_buf is not None:
+            evict_buf.zero_()
+        sa.attn_fwd(Q, K, V, O, scale=w.scale, causal=w.causal, scan_order=order)
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        if evict_buf is not None:
+            evict_buf.zero_()
+        starts[i].record(stream)
+        sa.attn_fwd(Q, K, V, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream)
+        stops[i].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    kernel_ms = sum(a.elapsed_time(b) for a, b in zip(starts, stops)) / steps
+    return wall_ms, kernel_ms
+
+
+def cpu_baseline(w, Q, K, V, target_seconds):
+    """Time the oracle, as it stands, on evenly spaced query rows of head (0, 0)."""
+    from oracle import attn_oracle
+    threads = attn_oracle.num_threads()
+    q, k, v = Q[:1, :1].cpu(), K[:1, :1].cpu(), V[:1, :1].cpu()
+
+    def run(n_rows):
+        rows = [int(i * w.N / n_rows) for i in range(n_rows)]
+        t0 = time.perf_counter()
+        attn_oracle.attention(q, k, v, w.scale, causal=w.causal, rows=rows)
+        dt = time.perf_counter() - t0
+        # flops of exactly these rows (a causal row i has i+1 visible keys)
+        fl = sum(4.0 * ((r + 1) if w.causal else w.N) * w.d for r in rows)
+        return dt, fl
+
+    n0 = min(w.N, 64)
+    dt0, _ = run(n0)
+    n = int(min(w.N, max(n0, n0 * target_seconds / max(dt0, 1e-4))))
+    dt, fl = run(n)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} evenly spaced query rows of head (0,0) of {w.name}: {fl:.3e} flop in {dt:.2f} s, fp64",
+            "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2601_16032_amd import binding as sa
+    from paper_2601_16032_amd import workloads
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    sa.lib()   # raises if the HIP library is not built: there is no fallback
+    torch.cuda.set_device(0)
+    w = workloads.WORKLOADS[args.workload]
+    Q, K, V = workloads.make_qkv(w)
+    Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+    # the output type the parity tests use for this workload: fp16 for fp16 inputs, fp32 for bf16 inputs
+    o_dtype = torch.float16 if w.dtype == "f16" else torch.float32
+    O = torch.empty(Qd.shape, dtype=o_dtype, device="cuda")
+    evict_buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda") if args.evict else None
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal)
+    orders = ["sawtooth", "cyclic"] if args.scan_order == "both" else [args.scan_order]
+    res = {}
+    for order in orders:
+        wall_ms, kernel_ms = time_order(sa, torch, Qd, Kd, Vd, O, w, order, args.steps, args.warmup, evict_buf)
+        res[order] = {"ms_per_step": wall_ms, "kernel_ms": kernel_ms,
+                      "tflops": w.flops / (kernel_ms * 1e-3) / 1e12,
+                      "tflops_wall": w.flops / (wall_ms * 1e-3) / 1e12}
+    head = orders[0]
+    r = res[head]
+    out = {
+        "metric": "attention fwd TFLOP/s (fp16, N=16k, d=128) + L2 miss count, sawtooth vs cyclic",
+        "value": r["tflops_wall"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": w.causal,
+                   "scan_order": head, "out_dtype": str(o_dtype).replace("torch.", ""), "flops_per_step": w.flops,
+                   "launch": info, "cache_cold_steps": bool(args.evict)},
+        "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_PEAK_TFLOPS_16BIT,
+                     "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_PEAK_TFLOPS_16BIT,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, head)),
+                     "kernel_ms": r["kernel_ms"]},
+        "scan_orders": {o: {"tflops": res[o]["tflops"], "kernel_ms": res[o]["kernel_ms"],
+                            "tcc_miss": MEASURED_TCC_MISS.get((args.workload, o))} for o in orders},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, Q, K, V, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -62,14 +62,25 @@ struct Params {
     Schedule sched;
 };
 
+// LDS tile layout.  A tile is 64 rows of D 16-bit elements, rows packed back to back (no padding, so
+// that one wavefront-wide direct global->LDS load, which writes 64 x 16 contiguous bytes, fills whole
+// rows).  Inside a row the 16-byte chunks are permuted: chunk cc of row r sits at chunk position
+// cc ^ swz(r).  swz is chosen so that both read patterns are free of bank conflicts:
+//   * K operand: 16 lanes read the same chunk of 16 consecutive rows          -> swz distinct over them
+//   * V operand (ds_read_b64_tr_b16): 32 lanes read 4 consecutive rows x 64 B -> the rows land in
+//     four different 64-byte bank groups.
 template <int D>
 struct Geo {
     static constexpr int kRowBytes = D * 2;
-    static constexpr int kStride = kRowBytes + 16;           // LDS row pitch, padded against bank conflicts
-    static constexpr int kTileBytes = kTileKV * kStride;     // one K or V tile in LDS
-    static constexpr int kChunksPerRow = D / 8;              // 16-byte chunks per row
-    static constexpr int kChunksPerThread = kTileKV * kChunksPerRow / kThreads;
-    static constexpr int kLdsBytes = 4 * kTileBytes;         // K0 K1 V0 V1
+    static constexpr int kChunksPerRow = D / 8;                       // 16-byte chunks per row
+    static constexpr int kTile = kTileKV * kRowBytes;                 // one K or V tile in LDS
+    static constexpr int kRowsPerWaveLoad = 1024 / kRowBytes;         // rows one 64-lane x 16 B load covers
+    static constexpr int kLoadsPerWave = kTile / 1024 / (kThreads / 64);
+    static constexpr int kLdsBytes = 4 * kTile;                       // K0 K1 V0 V1
+    __device__ static __forceinline__ int swz(int row) {
+        if constexpr (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+        else return ((row & 2) << 1) | ((row >> 2) & 3);              // u = row>>1: (u&1)<<2 | (u>>1)&3
+    }
 };
 
 template <bool BF16>
@@ -93,188 +104,327 @@ __device__ __forceinline__ u4 bf16x8_to_f16x8(u4 w) {
     return r;
 }
 
+// Where this thread's 16-byte chunks of a 64-row tile come from and go to.  Wavefront w, load i
+// covers LDS bytes [(i*4 + w) * 1024, +1024): lane l writes chunk position l % CPR of row
+// base + l / CPR and therefore fetches source chunk (l % CPR) ^ swz(row) of that row.
 template <int D>
-__device__ __forceinline__ void load_tile(const char* base, int kv0, int N, int tid, u4 (&reg)[Geo<D>::kChunksPerThread]) {
+struct TileMap {
+    int row[Geo<D>::kLoadsPerWave];            // row inside the tile
+    unsigned src_byte[Geo<D>::kLoadsPerWave];  // byte offset of the source chunk inside its row
+    __device__ __forceinline__ TileMap(int wave, int lane) {
+        using G = Geo<D>;
 #pragma unroll
-    for (int i = 0; i < Geo<D>::kChunksPerThread; ++i) {
-        int id = tid + i * kThreads;
-        int row = id / Geo<D>::kChunksPerRow, cc = id % Geo<D>::kChunksPerRow;
-        u4 v = {0u, 0u, 0u, 0u};
-        if (kv0 + row < N) v = *reinterpret_cast<const u4*>(base + (size_t)(kv0 + row) * Geo<D>::kRowBytes + cc * 16);
-        reg[i] = v;
+        for (int i = 0; i < G::kLoadsPerWave; ++i) {
+            const int r = (i * 4 + wave) * G::kRowsPerWaveLoad + lane / G::kChunksPerRow;
+            row[i] = r;
+            src_byte[i] = ((lane % G::kChunksPerRow) ^ G::swz(r)) * 16;
+        }
+    }
+};
+
+// Direct global -> LDS copy of one tile (no registers in between).  Rows at or beyond N re-read row
+// N-1: always valid memory and finite data; such keys are masked before use.  `wave` is uniform.
+template <int D>
+__device__ __forceinline__ void tile_to_lds(const char* head, int kv0, int N, const TileMap<D>& tm, int wave,
+                                            LDS_PTR(char) dst) {
+    using G = Geo<D>;
+#pragma unroll
+    for (int i = 0; i < G::kLoadsPerWave; ++i) {
+        int r = kv0 + tm.row[i];
+        r = r < N ? r : N - 1;
+        const unsigned off = (unsigned)r * G::kRowBytes + tm.src_byte[i];   // N*d*2 < 2^32
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(head + off),
+                                         (LDS_PTR(void))(dst + (i * 4 + wave) * 1024), 16, 0, 0);
     }
 }
 
-template <int D, bool CONVERT>
-__device__ __forceinline__ void store_tile(char* lds, int tid, const u4 (&reg)[Geo<D>::kChunksPerThread]) {
+// Register path for V in bfloat16 (converted to binary16 before it reaches LDS).
+template <int D>
+__device__ __forceinline__ void tile_to_regs(const char* head, int kv0, int N, const TileMap<D>& tm,
+                                             u4 (&reg)[Geo<D>::kLoadsPerWave]) {
+    using G = Geo<D>;
 #pragma unroll
-    for (int i = 0; i < Geo<D>::kChunksPerThread; ++i) {
-        int id = tid + i * kThreads;
-        int row = id / Geo<D>::kChunksPerRow, cc = id % Geo<D>::kChunksPerRow;
-        u4 v = reg[i];
-        if constexpr (CONVERT) v = bf16x8_to_f16x8(v);
-        *reinterpret_cast<u4*>(lds + row * Geo<D>::kStride + cc * 16) = v;
+    for (int i = 0; i < G::kLoadsPerWave; ++i) {
+        int r = kv0 + tm.row[i];
+        r = r < N ? r : N - 1;
+        const unsigned off = (unsigned)r * G::kRowBytes + tm.src_byte[i];
+        reg[i] = *reinterpret_cast<const u4*>(head + off);
     }
+}
+template <int D>
+__device__ __forceinline__ void regs_to_lds_f16(const u4 (&reg)[Geo<D>::kLoadsPerWave], int wave, int lane, LDS_PTR(char) dst) {
+    using G = Geo<D>;
+#pragma unroll
+    for (int i = 0; i < G::kLoadsPerWave; ++i)
+        *(LDS_PTR(u4))(dst + (i * 4 + wave) * 1024 + lane * 16) = bf16x8_to_f16x8(reg[i]);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Exchange between the lanes l and l^32, the two lanes that share a query row.  v_permlane32_swap
+// swaps the upper 32 lanes of its first operand with the lower 32 lanes of its second; starting
+// from two copies of x this leaves (lower half of x everywhere, upper half of x everywhere).
+__device__ __forceinline__ void lane_pair(float x, float& lower, float& upper) {
+    unsigned a = __builtin_bit_cast(unsigned, x), b = a;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+    lower = __builtin_bit_cast(float, a);
+    upper = __builtin_bit_cast(float, b);
+}
+__device__ __forceinline__ float pair_max(float x) {
+    float lo, hi;
+    lane_pair(x, lo, hi);
+    return fmaxf(lo, hi);
+}
+__device__ __forceinline__ float pair_sum(float x) {
+    float lo, hi;
+    lane_pair(x, lo, hi);
+    return lo + hi;
+}
+
+// The running maximum is only raised when a tile's maximum exceeds it by more than this many
+// binades; until then probabilities are taken relative to the older, smaller reference and may be
+// as large as 2^kRescaleSlack.  O and the running sum stay consistent, so the result is unchanged;
+// it saves rescaling the whole accumulator on almost every tile.
+constexpr float kRescaleSlack = 8.0f;
+
+// One K/V tile for one wavefront: S^T = K Q^T, softmax update, O^T += V^T P^T.
+// kt / vt: base of the K / V tile in LDS.
+template <int D, bool BF16, bool CAUSAL, bool MASKED>
+__device__ __forceinline__ void compute_tile(LDS_PTR(char) kt, LDS_PTR(char) vt, const u4 (&qf)[D / 16],
+                                             f16v (&o)[D / 32], float& M, float& L, float c, int kv0, int qrow,
+                                             int lane, int N) {
+    using G = Geo<D>;
+    constexpr int KS = D / 16, DB = D / 32;
+    const int g = lane >> 5, ln = lane & 31;
+    // ---- S^T = K_j Q_i^T : two 32(kv) x 32(q) blocks.  Lane reads chunk 2*ks+g of rows ln and 32+ln;
+    //      swz(32 + ln) == swz(ln) for both head sizes.
+    f16v s[2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
+    {
+        LDS_PTR(char) krow = kt + ln * G::kRowBytes;
+        const int sw = G::swz(ln);
+        // operands are fetched two steps ahead of the MFMA that consumes them
+        u4 a[KS][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int off = ((2 * ks + g) ^ sw) * 16;
+            a[ks][0] = *(LDS_PTR(u4))(krow + off);
+            a[ks][1] = *(LDS_PTR(u4))(krow + 32 * G::kRowBytes + off);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 2 < KS) {
+                const int off = ((2 * (ks + 2) + g) ^ sw) * 16;
+                a[ks + 2][0] = *(LDS_PTR(u4))(krow + off);
+                a[ks + 2][1] = *(LDS_PTR(u4))(krow + 32 * G::kRowBytes + off);
+            }
+            s[0] = mfma_16bit<BF16>(a[ks][0], qf[ks], s[0]);
+            s[1] = mfma_16bit<BF16>(a[ks][1], qf[ks], s[1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    // ---- mask: keys at or beyond N, and keys after the query under the causal mask
+    unsigned masked = 0u;
+    if constexpr (MASKED) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kv = kv0 + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
+                const bool m = (kv >= N) || (CAUSAL && kv > qrow);
+                if (m) { masked |= 1u << (16 * b + r); s[b][r] = -INFINITY; }
+            }
+    }
+    // ---- online softmax in the log2 domain
+    float mx = s[0][0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
+    mx = pair_max(mx);
+    const float tmax = mx * c;
+    if (__builtin_amdgcn_ballot_w64(tmax > M + kRescaleSlack) != 0) {
+        const float Mnew = fmaxf(M, tmax);
+        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(M - Mnew);
+        M = Mnew;
+        L *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+    }
+    const float Mref = (MASKED && M == -INFINITY) ? 0.f : M;
+    u4 pf[4];
+    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            u4 w;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int r = 8 * h + 2 * i;
+                float x0 = fast_exp2(__builtin_fmaf(s[b][r], c, -Mref));
+                float x1 = fast_exp2(__builtin_fmaf(s[b][r + 1], c, -Mref));
+                if constexpr (MASKED) {
+                    if ((masked >> (16 * b + r)) & 1u) x0 = 0.f;
+                    if ((masked >> (16 * b + r + 1)) & 1u) x1 = 0.f;
+                }
+                const h2 ph = __builtin_convertvector(f2{x0, x1}, h2);
+                // running sum of the rounded probabilities, the values the second product uses
+                L = __builtin_amdgcn_fdot2(ph, ones, L, false);
+                w[i] = __builtin_bit_cast(unsigned, ph);
+            }
+            pf[2 * b + h] = w;
+        }
+    // ---- O^T += V_j^T P^T.  Source lane 4e + c of a 16-lane group addresses row e, 8-byte column
+    //      chunk c of the 4 x 16 block whose columns the group's lanes receive.
+    {
+        const int vrow = 4 * g + ((lane & 15) >> 2);              // + 16*ks + 8*h
+        const int chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);   // + 4*db : 16-byte chunk in the row
+        const int half = (lane & 1) * 8;                          // which 8 bytes of that chunk
+        auto read_a = [&](int idx) -> s8 {
+            const int ks = idx / DB, db = idx % DB;
+            const int r0 = vrow + 16 * ks, r1 = r0 + 8;
+            const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_PTR(s4))(vt + r0 * G::kRowBytes + half + (((4 * db + chunk) ^ G::swz(r0)) * 16)));
+            const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (LDS_PTR(s4))(vt + r1 * G::kRowBytes + half + (((4 * db + chunk) ^ G::swz(r1)) * 16)));
+            return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        };
+        constexpr int NSTEP = 4 * DB, AHEAD = 2;
+        s8 av[NSTEP];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int idx = 0; idx < AHEAD; ++idx) av[idx] = read_a(idx);
+#pragma unroll
+        for (int idx = 0; idx < NSTEP; ++idx) {
+            if (idx + AHEAD < NSTEP) av[idx + AHEAD] = read_a(idx + AHEAD);
+            const int ks = idx / DB, db = idx % DB;
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[ks]), o[db], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// Per-workgroup state of one query tile that the K/V loop carries along.
+template <int D>
+struct TileState {
+    u4 qf[D / 16];      // Q^T as B operand: lane holds Q[qrow][16*ks + 8*g .. +7]
+    f16v o[D / 32];     // O^T accumulator
+    float M;            // reference maximum of score*c (log2 domain), same in both lanes of a pair
+    float L;            // this lane's partial running sum
+};
+
+// K/V iterations [it_begin, it_end) of one query tile, all with or all without the mask code.
+// Iteration `it` uses tile j0 + it*step out of LDS buffer it&1 and, while computing, fetches the
+// tile of iteration it+1 (if it < n_total-1) into the other buffer.
+template <int D, bool BF16, bool CAUSAL, bool MASKED>
+__device__ __forceinline__ void kv_loop(TileState<D>& st, const char* Kh, const char* Vh, int N, float c,
+                                        int j0, int step, int it_begin, int it_end, int n_total, int qw0,
+                                        int qrow, bool wave_has_rows, const TileMap<D>& tm, int wave, int lane,
+                                        LDS_PTR(char) lds) {
+    using G = Geo<D>;
+    u4 vreg[G::kLoadsPerWave];   // only used for bfloat16 inputs
+    for (int it = it_begin; it < it_end; ++it) {
+        const int cur = it & 1;
+        const int j = j0 + it * step;
+        const int kv0 = j * kTileKV;
+        const bool more = it + 1 < n_total;
+        if (more) {
+            tile_to_lds<D>(Kh, (j + step) * kTileKV, N, tm, wave, lds + (cur ^ 1) * G::kTile);
+            if constexpr (BF16) tile_to_regs<D>(Vh, (j + step) * kTileKV, N, tm, vreg);
+            else tile_to_lds<D>(Vh, (j + step) * kTileKV, N, tm, wave, lds + (2 + (cur ^ 1)) * G::kTile);
+        }
+        const bool active = wave_has_rows && (!CAUSAL || kv0 <= qw0 + 31);
+        if (active)
+            compute_tile<D, BF16, CAUSAL, MASKED>(lds + cur * G::kTile, lds + (2 + cur) * G::kTile, st.qf, st.o, st.M,
+                                                  st.L, c, kv0, qrow, lane, N);
+        if (more) {
+            if constexpr (BF16) regs_to_lds_f16<D>(vreg, wave, lane, lds + (2 + (cur ^ 1)) * G::kTile);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
+        }
+        __syncthreads();
+    }
+}
+
 // One query tile (Alg. 1 body): rows [t*128, t*128+128) of head `hh`, K/V tiles j0, j0+step, ... (nkv of them).
 template <int D, bool BF16, bool CAUSAL>
-__device__ __forceinline__ void process_q_tile(const Params& p, int hh, int t, int j0, int step, int nkv, char* smem) {
+__device__ __forceinline__ void process_q_tile(const Params& p, int hh, int t, int j0, int step, int nkv, LDS_PTR(char) lds) {
     using G = Geo<D>;
     constexpr int KS = D / 16;    // MFMA steps along d for S^T
     constexpr int DB = D / 32;    // 32-row blocks of O^T
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 5, ln = lane & 31;
     const int N = p.N;
     const size_t head_off = (size_t)hh * N * G::kRowBytes;
     const char* Qh = static_cast<const char*>(p.Q) + head_off;
     const char* Kh = static_cast<const char*>(p.K) + head_off;
     const char* Vh = static_cast<const char*>(p.V) + head_off;
-    char* Kl[2] = {smem, smem + G::kTileBytes};
-    char* Vl[2] = {smem + 2 * G::kTileBytes, smem + 3 * G::kTileBytes};
 
     const int qw0 = t * kTileQ + wave * 32;   // first query row of this wavefront
     const int qrow = qw0 + ln;                // this lane's query row (column of S^T)
     const bool wave_has_rows = qw0 < N;
 
-    // Q^T as B operand: lane holds Q[qrow][16*ks + 8*g .. +7]
-    u4 qf[KS];
+    TileState<D> st;
+    {   // rows beyond N repeat row N-1 (computed, never stored)
+        const int qr = qrow < N ? qrow : N - 1;
+        const char* qp = Qh + (size_t)qr * G::kRowBytes + g * 16;
+        const unsigned flip = p.negate_q ? 0x80008000u : 0u;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        u4 v = {0u, 0u, 0u, 0u};
-        if (qrow < N) v = *reinterpret_cast<const u4*>(Qh + (size_t)qrow * G::kRowBytes + ks * 32 + g * 16);
-        if (p.negate_q) { v[0] ^= 0x80008000u; v[1] ^= 0x80008000u; v[2] ^= 0x80008000u; v[3] ^= 0x80008000u; }
-        qf[ks] = v;
+        for (int ks = 0; ks < KS; ++ks) {
+            u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
+            v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
+            st.qf[ks] = v;
+        }
     }
-
-    f16v o[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float M = -INFINITY;   // running max of score*c (log2 domain)
-    float L = 0.f;         // this lane's partial running sum
+        for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+    st.M = -INFINITY;
+    st.L = 0.f;
     const float c = p.c;
+    const TileMap<D> tm(wave, lane);
 
-    u4 kreg[G::kChunksPerThread], vreg[G::kChunksPerThread];
-    load_tile<D>(Kh, j0 * kTileKV, N, tid, kreg);
-    load_tile<D>(Vh, j0 * kTileKV, N, tid, vreg);
-    store_tile<D, false>(Kl[0], tid, kreg);
-    store_tile<D, BF16>(Vl[0], tid, vreg);
+    // first tile
+    tile_to_lds<D>(Kh, j0 * kTileKV, N, tm, wave, lds);
+    if constexpr (BF16) {
+        u4 vreg[G::kLoadsPerWave];
+        tile_to_regs<D>(Vh, j0 * kTileKV, N, tm, vreg);
+        regs_to_lds_f16<D>(vreg, wave, lane, lds + 2 * G::kTile);
+    } else {
+        tile_to_lds<D>(Vh, j0 * kTileKV, N, tm, wave, lds + 2 * G::kTile);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
 
-    // per-lane byte offsets inside a tile
-    const int k_off = ln * G::kStride + g * 16;
-    const int v_off = (4 * g + ((lane & 15) >> 2)) * G::kStride + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-
-    for (int it = 0; it < nkv; ++it) {
-        const int cur = it & 1;
-        const int j = j0 + it * step;
-        const int kv0 = j * kTileKV;
-        const bool more = it + 1 < nkv;
-        if (more) {
-            load_tile<D>(Kh, (j + step) * kTileKV, N, tid, kreg);
-            load_tile<D>(Vh, (j + step) * kTileKV, N, tid, vreg);
-        }
-        const bool active = wave_has_rows && (!CAUSAL || kv0 <= qw0 + 31);
-        if (active) {
-            // ---- S^T = K_j Q_i^T : two 32(kv) x 32(q) blocks
-            f16v s[2];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
-            const char* kl = Kl[cur] + k_off;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                u4 a0 = *reinterpret_cast<const u4*>(kl + ks * 32);
-                u4 a1 = *reinterpret_cast<const u4*>(kl + 32 * G::kStride + ks * 32);
-                s[0] = mfma_16bit<BF16>(a0, qf[ks], s[0]);
-                s[1] = mfma_16bit<BF16>(a1, qf[ks], s[1]);
-            }
-            // ---- mask: keys beyond N, and keys after the query under the causal mask
-            const bool need_mask = (kv0 + kTileKV > N) || (CAUSAL && kv0 + kTileKV - 1 > qw0);
-            unsigned masked = 0u;
-            if (need_mask) {
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        int kv = kv0 + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
-                        bool m = (kv >= N) || (CAUSAL && kv > qrow);
-                        if (m) { masked |= 1u << (16 * b + r); s[b][r] = -INFINITY; }
-                    }
-            }
-            // ---- online softmax (log2 domain)
-            float mx = s[0][0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[0][r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float Mnew = fmaxf(M, mx * c);
-            const float Muse = (Mnew == -INFINITY) ? 0.f : Mnew;
-            const float alpha = fast_exp2(M - Muse);
-            M = Mnew;
-            float lsum = 0.f;
-            u4 pf[4];
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                float pv[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    float x = fast_exp2(__builtin_fmaf(s[b][r], c, -Muse));
-                    if (need_mask && ((masked >> (16 * b + r)) & 1u)) x = 0.f;
-                    pv[r] = x;
-                    lsum += x;
-                }
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    u4 w;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        f2 x2 = {pv[8 * h + 2 * i], pv[8 * h + 2 * i + 1]};
-                        w[i] = __builtin_bit_cast(unsigned, __builtin_convertvector(x2, h2));
-                    }
-                    pf[2 * b + h] = w;
-                }
-            }
-            L = L * alpha + lsum;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-            // ---- O^T += V_j^T P^T
-            const char* vl = Vl[cur] + v_off;
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const char* a = vl + (16 * ks) * G::kStride + db * 64;
-                    s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(a));
-                    s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(a + 8 * G::kStride));
-                    s8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av), __builtin_bit_cast(h8, pf[ks]), o[db], 0, 0, 0);
-                }
-            }
-        }
-        if (more) {
-            store_tile<D, false>(Kl[cur ^ 1], tid, kreg);
-            store_tile<D, BF16>(Vl[cur ^ 1], tid, vreg);
-        }
-        __syncthreads();
+    // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
+    // the tiles that reach past the first row of this query tile.  They sit at one end of the scan.
+    const int kv_tiles = (N + kTileKV - 1) / kTileKV;
+    const int jm = CAUSAL ? (t * kTileQ) / kTileKV : ((N % kTileKV) ? kv_tiles - 1 : kv_tiles);
+    const int n_masked = nkv > jm ? nkv - jm : 0;
+    const int n_plain = nkv - n_masked;
+    if (step > 0) {
+        kv_loop<D, BF16, CAUSAL, false>(st, Kh, Vh, N, c, j0, step, 0, n_plain, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
+        kv_loop<D, BF16, CAUSAL, true>(st, Kh, Vh, N, c, j0, step, n_plain, nkv, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
+    } else {
+        kv_loop<D, BF16, CAUSAL, true>(st, Kh, Vh, N, c, j0, step, 0, n_masked, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
+        kv_loop<D, BF16, CAUSAL, false>(st, Kh, Vh, N, c, j0, step, n_masked, nkv, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
     }
 
     // ---- epilogue: O_i = acc / l  (the division Alg. 1 leaves implicit; Eq. 1 fixes it)
-    const float Ltot = L + __shfl_xor(L, 32, 64);
-    const float inv = 1.0f / Ltot;
+    const float inv = 1.0f / pair_sum(st.L);
     if (qrow < N) {
         const size_t orow = ((size_t)hh * N + qrow) * D;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
-                f4 v = {o[db][4 * rq] * inv, o[db][4 * rq + 1] * inv, o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv};
+                const f16v& o = st.o[db];
+                f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
                 const size_t col = 32 * db + 8 * rq + 4 * g;
                 if (p.o_dtype == SAWATTN_F32) {
                     *reinterpret_cast<f4*>(static_cast<float*>(p.O) + orow + col) = v;
@@ -308,7 +458,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
                 int32_t* rec = p.trace + ((size_t)blockIdx.x * p.max_local + local) * 4;
                 rec[0] = hh; rec[1] = t; rec[2] = j0; rec[3] = j0 + (nkv - 1) * step;
             }
-            process_q_tile<D, BF16, CAUSAL>(p, hh, t, j0, step, nkv, smem);
+            process_q_tile<D, BF16, CAUSAL>(p, hh, t, j0, step, nkv, (LDS_PTR(char))smem);
             ++local;
         }
     }
