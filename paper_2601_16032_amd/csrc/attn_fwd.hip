@@ -25,6 +25,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <utility>
 
 #include "sawattn.h"
 #include "schedule.h"
@@ -104,59 +105,113 @@ __device__ __forceinline__ u4 bf16x8_to_f16x8(u4 w) {
     return r;
 }
 
-// Where this thread's 16-byte chunks of a 64-row tile come from and go to.  Wavefront w, load i
-// covers LDS bytes [(i*4 + w) * 1024, +1024): lane l writes chunk position l % CPR of row
-// base + l / CPR and therefore fetches source chunk (l % CPR) ^ swz(row) of that row.
+// Compile-time loop: f(std::integral_constant<int, I>) for I in [0, N).
+template <int N, typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl<N>(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+// Lane-constant addresses, computed once per kernel.
+//
+// Tile fill: wavefront w, load i covers LDS bytes [(i*4 + w) * 1024, +1024) of a tile: lane l
+// writes chunk position l % CPR of row (i*4+w)*rows_per_load + l / CPR and therefore fetches source
+// chunk (l % CPR) ^ swz(row) of that row.
+// K operand (S^T = K Q^T): lane reads chunk 2*ks + g of rows ln and 32 + ln (same swz for both).
+// V operand (ds_read_b64_tr_b16): source lane 4e + c of a 16-lane group addresses row e, 8-byte
+// column chunk c of the 4 x 16 block whose columns the lanes of the group receive; the rows are
+// kv = 16*ks + 8*h + 4*g + e, so that the contraction slots line up with the registers of P^T.
 template <int D>
-struct TileMap {
-    int row[Geo<D>::kLoadsPerWave];            // row inside the tile
-    unsigned src_byte[Geo<D>::kLoadsPerWave];  // byte offset of the source chunk inside its row
-    __device__ __forceinline__ TileMap(int wave, int lane) {
-        using G = Geo<D>;
+struct LaneMap {
+    using G = Geo<D>;
+    unsigned fill_src[G::kLoadsPerWave];   // row * row_bytes + byte offset of the source chunk
+    unsigned fill_dst;                     // wave * 1024 (+ i * 4096): LDS byte offset inside the tile
+    unsigned k_rd[D / 16];                 // byte offset inside a K tile, MFMA step ks, rows ln (+32 rows: +32*row_bytes)
+    unsigned v_rd[D / 32][2];              // byte offset inside a V tile for [db][h], kv step 0 (+ks: +16*row_bytes*ks)
+    __device__ __forceinline__ LaneMap(int wave, int lane) {
+        const int g = lane >> 5, ln = lane & 31;
 #pragma unroll
         for (int i = 0; i < G::kLoadsPerWave; ++i) {
             const int r = (i * 4 + wave) * G::kRowsPerWaveLoad + lane / G::kChunksPerRow;
-            row[i] = r;
-            src_byte[i] = ((lane % G::kChunksPerRow) ^ G::swz(r)) * 16;
+            fill_src[i] = r * G::kRowBytes + ((lane % G::kChunksPerRow) ^ G::swz(r)) * 16;
         }
+        fill_dst = wave * 1024;
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) k_rd[ks] = ln * G::kRowBytes + ((2 * ks + g) ^ G::swz(ln)) * 16;
+        const int vrow = 4 * g + ((lane & 15) >> 2);
+        const int chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+        const int half = (lane & 1) * 8;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int r = vrow + 8 * h;     // swz(r + 16*ks) == swz(r)
+                v_rd[db][h] = r * G::kRowBytes + ((4 * db + chunk) ^ G::swz(r)) * 16 + half;
+            }
     }
 };
 
-// Direct global -> LDS copy of one tile (no registers in between).  Rows at or beyond N re-read row
-// N-1: always valid memory and finite data; such keys are masked before use.  `wave` is uniform.
+// One 64-lane x 16-byte direct global -> LDS load: lane l's 16 bytes from base + voff land at LDS
+// byte address lds_addr + 16*l.  Issued as inline assembly so that the compiler does not treat every
+// later LDS read as depending on it (it would wait for the whole next tile before reading the
+// current one); the landing is awaited explicitly with wait_tile_landed() before the barrier that
+// publishes the tile.
+__device__ __forceinline__ void load_to_lds_16B(const char* base, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+__device__ __forceinline__ void wait_tile_landed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Per-lane byte offsets (relative to the head's base) of this lane's chunks of tile j.  A ragged
+// last tile re-reads row N-1 for the rows beyond N: always valid memory and finite data; such
+// keys are masked before use.
 template <int D>
-__device__ __forceinline__ void tile_to_lds(const char* head, int kv0, int N, const TileMap<D>& tm, int wave,
-                                            LDS_PTR(char) dst) {
+__device__ __forceinline__ void tile_offsets(int j, int N, const LaneMap<D>& lm, unsigned (&off)[Geo<D>::kLoadsPerWave]) {
     using G = Geo<D>;
+    const int kv0 = j * kTileKV;
+    if (kv0 + kTileKV <= N) {
 #pragma unroll
-    for (int i = 0; i < G::kLoadsPerWave; ++i) {
-        int r = kv0 + tm.row[i];
-        r = r < N ? r : N - 1;
-        const unsigned off = (unsigned)r * G::kRowBytes + tm.src_byte[i];   // N*d*2 < 2^32
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(head + off),
-                                         (LDS_PTR(void))(dst + (i * 4 + wave) * 1024), 16, 0, 0);
+        for (int i = 0; i < G::kLoadsPerWave; ++i) off[i] = lm.fill_src[i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < G::kLoadsPerWave; ++i) {
+            const unsigned row = lm.fill_src[i] / G::kRowBytes, chunk = lm.fill_src[i] % G::kRowBytes;
+            unsigned r = kv0 + row;
+            r = r < (unsigned)N ? r : (unsigned)N - 1;
+            off[i] = (r - kv0) * G::kRowBytes + chunk;   // may wrap below zero: added to the tile base mod 2^32
+        }
     }
+}
+
+// Direct global -> LDS copy of tile j of a head into the tile at LDS byte address dst.
+template <int D>
+__device__ __forceinline__ void tile_to_lds(const char* head, int j, const unsigned (&off)[Geo<D>::kLoadsPerWave],
+                                            const LaneMap<D>& lm, unsigned dst) {
+    using G = Geo<D>;
+    const char* base = head + (size_t)j * kTileKV * G::kRowBytes;
+#pragma unroll
+    for (int i = 0; i < G::kLoadsPerWave; ++i) load_to_lds_16B(base, off[i], dst + lm.fill_dst + i * 4096);
 }
 
 // Register path for V in bfloat16 (converted to binary16 before it reaches LDS).
 template <int D>
-__device__ __forceinline__ void tile_to_regs(const char* head, int kv0, int N, const TileMap<D>& tm,
+__device__ __forceinline__ void tile_to_regs(const char* head, int j, const unsigned (&off)[Geo<D>::kLoadsPerWave],
                                              u4 (&reg)[Geo<D>::kLoadsPerWave]) {
     using G = Geo<D>;
+    const char* base = head + (size_t)j * kTileKV * G::kRowBytes;
 #pragma unroll
-    for (int i = 0; i < G::kLoadsPerWave; ++i) {
-        int r = kv0 + tm.row[i];
-        r = r < N ? r : N - 1;
-        const unsigned off = (unsigned)r * G::kRowBytes + tm.src_byte[i];
-        reg[i] = *reinterpret_cast<const u4*>(head + off);
-    }
+    for (int i = 0; i < G::kLoadsPerWave; ++i) reg[i] = *reinterpret_cast<const u4*>(base + off[i]);
 }
 template <int D>
-__device__ __forceinline__ void regs_to_lds_f16(const u4 (&reg)[Geo<D>::kLoadsPerWave], int wave, int lane, LDS_PTR(char) dst) {
+__device__ __forceinline__ void regs_to_lds_f16(const u4 (&reg)[Geo<D>::kLoadsPerWave], const LaneMap<D>& lm, int lane,
+                                                LDS_PTR(char) dst) {
     using G = Geo<D>;
 #pragma unroll
     for (int i = 0; i < G::kLoadsPerWave; ++i)
-        *(LDS_PTR(u4))(dst + (i * 4 + wave) * 1024 + lane * 16) = bf16x8_to_f16x8(reg[i]);
+        *(LDS_PTR(u4))(dst + lm.fill_dst + i * 4096 + lane * 16) = bf16x8_to_f16x8(reg[i]);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -187,40 +242,56 @@ __device__ __forceinline__ float pair_sum(float x) {
 // it saves rescaling the whole accumulator on almost every tile.
 constexpr float kRescaleSlack = 8.0f;
 
-// One K/V tile for one wavefront: S^T = K Q^T, softmax update, O^T += V^T P^T.
-// kt / vt: base of the K / V tile in LDS.
+// Per-wavefront state of one query tile that the K/V loop carries along.
+template <int D>
+struct TileState {
+    u4 qf[D / 16];      // Q^T as B operand: lane holds Q[qrow][16*ks + 8*g .. +7]
+    f16v o[D / 32];     // O^T accumulator
+    float M;            // reference maximum of score*c (log2 domain), same in both lanes of a pair
+    float L;            // this lane's partial running sum
+};
+
+// This lane's LDS read addresses for the K/V buffer pair in use; flipped to the other pair after
+// every iteration.
+template <int D>
+struct ReadAddr {
+    unsigned k[D / 16];       // K operand, MFMA step ks, row ln (+32 rows: +32*row_bytes)
+    unsigned v[D / 32][2];    // V operand [db][h], kv step 0 (+ks: +16*row_bytes*ks)
+    __device__ __forceinline__ void flip(int delta) {
+#pragma unroll
+        for (int ks = 0; ks < D / 16; ++ks) k[ks] += delta;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) { v[db][0] += delta; v[db][1] += delta; }
+    }
+};
+
+// One K/V tile for one wavefront out of the LDS buffers `ra` points at: S^T = K Q^T, softmax
+// update, O^T += V^T P^T.
 template <int D, bool BF16, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void compute_tile(LDS_PTR(char) kt, LDS_PTR(char) vt, const u4 (&qf)[D / 16],
-                                             f16v (&o)[D / 32], float& M, float& L, float c, int kv0, int qrow,
-                                             int lane, int N) {
+__device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>& ra, float c, int kv0, int qrow, int lane,
+                                             int N) {
     using G = Geo<D>;
     constexpr int KS = D / 16, DB = D / 32;
-    const int g = lane >> 5, ln = lane & 31;
-    // ---- S^T = K_j Q_i^T : two 32(kv) x 32(q) blocks.  Lane reads chunk 2*ks+g of rows ln and 32+ln;
-    //      swz(32 + ln) == swz(ln) for both head sizes.
+    const int g = lane >> 5;
+    // ---- S^T = K_j Q_i^T : two 32(kv) x 32(q) blocks; operands fetched two steps ahead
     f16v s[2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[0][r] = 0.f; s[1][r] = 0.f; }
     {
-        LDS_PTR(char) krow = kt + ln * G::kRowBytes;
-        const int sw = G::swz(ln);
-        // operands are fetched two steps ahead of the MFMA that consumes them
         u4 a[KS][2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            const int off = ((2 * ks + g) ^ sw) * 16;
-            a[ks][0] = *(LDS_PTR(u4))(krow + off);
-            a[ks][1] = *(LDS_PTR(u4))(krow + 32 * G::kRowBytes + off);
+            a[ks][0] = *(LDS_PTR(u4))(size_t)(ra.k[ks]);
+            a[ks][1] = *(LDS_PTR(u4))(size_t)(ra.k[ks] + 32 * G::kRowBytes);
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if (ks + 2 < KS) {
-                const int off = ((2 * (ks + 2) + g) ^ sw) * 16;
-                a[ks + 2][0] = *(LDS_PTR(u4))(krow + off);
-                a[ks + 2][1] = *(LDS_PTR(u4))(krow + 32 * G::kRowBytes + off);
+                a[ks + 2][0] = *(LDS_PTR(u4))(size_t)(ra.k[ks + 2]);
+                a[ks + 2][1] = *(LDS_PTR(u4))(size_t)(ra.k[ks + 2] + 32 * G::kRowBytes);
             }
-            s[0] = mfma_16bit<BF16>(a[ks][0], qf[ks], s[0]);
-            s[1] = mfma_16bit<BF16>(a[ks][1], qf[ks], s[1]);
+            s[0] = mfma_16bit<BF16>(a[ks][0], st.qf[ks], s[0]);
+            s[1] = mfma_16bit<BF16>(a[ks][1], st.qf[ks], s[1]);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -244,19 +315,20 @@ __device__ __forceinline__ void compute_tile(LDS_PTR(char) kt, LDS_PTR(char) vt,
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
     mx = pair_max(mx);
     const float tmax = mx * c;
-    if (__builtin_amdgcn_ballot_w64(tmax > M + kRescaleSlack) != 0) {
-        const float Mnew = fmaxf(M, tmax);
-        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(M - Mnew);
-        M = Mnew;
-        L *= alpha;
+    if (__builtin_amdgcn_ballot_w64(tmax > st.M + kRescaleSlack) != 0) {
+        const float Mnew = fmaxf(st.M, tmax);
+        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st.M - Mnew);
+        st.M = Mnew;
+        st.L *= alpha;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+            for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
     }
-    const float Mref = (MASKED && M == -INFINITY) ? 0.f : M;
+    const float Mref = (MASKED && st.M == -INFINITY) ? 0.f : st.M;
     u4 pf[4];
     const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    float L = st.L;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -278,22 +350,16 @@ __device__ __forceinline__ void compute_tile(LDS_PTR(char) kt, LDS_PTR(char) vt,
             }
             pf[2 * b + h] = w;
         }
-    // ---- O^T += V_j^T P^T.  Source lane 4e + c of a 16-lane group addresses row e, 8-byte column
-    //      chunk c of the 4 x 16 block whose columns the group's lanes receive.
+    st.L = L;
+    // ---- O^T += V_j^T P^T : 4 kv steps x DB row blocks; V^T operands fetched AHEAD steps ahead
     {
-        const int vrow = 4 * g + ((lane & 15) >> 2);              // + 16*ks + 8*h
-        const int chunk = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);   // + 4*db : 16-byte chunk in the row
-        const int half = (lane & 1) * 8;                          // which 8 bytes of that chunk
+        constexpr int NSTEP = 4 * DB, AHEAD = 2;
         auto read_a = [&](int idx) -> s8 {
             const int ks = idx / DB, db = idx % DB;
-            const int r0 = vrow + 16 * ks, r1 = r0 + 8;
-            const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (LDS_PTR(s4))(vt + r0 * G::kRowBytes + half + (((4 * db + chunk) ^ G::swz(r0)) * 16)));
-            const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (LDS_PTR(s4))(vt + r1 * G::kRowBytes + half + (((4 * db + chunk) ^ G::swz(r1)) * 16)));
+            const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(ra.v[db][0] + ks * 16 * G::kRowBytes));
+            const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(ra.v[db][1] + ks * 16 * G::kRowBytes));
             return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         };
-        constexpr int NSTEP = 4 * DB, AHEAD = 2;
         s8 av[NSTEP];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -302,48 +368,42 @@ __device__ __forceinline__ void compute_tile(LDS_PTR(char) kt, LDS_PTR(char) vt,
         for (int idx = 0; idx < NSTEP; ++idx) {
             if (idx + AHEAD < NSTEP) av[idx + AHEAD] = read_a(idx + AHEAD);
             const int ks = idx / DB, db = idx % DB;
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[ks]), o[db], 0, 0, 0);
+            st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[ks]),
+                                                              st.o[db], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
 
-// Per-workgroup state of one query tile that the K/V loop carries along.
-template <int D>
-struct TileState {
-    u4 qf[D / 16];      // Q^T as B operand: lane holds Q[qrow][16*ks + 8*g .. +7]
-    f16v o[D / 32];     // O^T accumulator
-    float M;            // reference maximum of score*c (log2 domain), same in both lanes of a pair
-    float L;            // this lane's partial running sum
-};
-
 // K/V iterations [it_begin, it_end) of one query tile, all with or all without the mask code.
-// Iteration `it` uses tile j0 + it*step out of LDS buffer it&1 and, while computing, fetches the
-// tile of iteration it+1 (if it < n_total-1) into the other buffer.
+// Iteration `it` uses tile j0 + it*step out of LDS buffer pair it & 1 and, while computing,
+// fetches the tile of iteration it+1 (if it + 1 < n_total) into the other pair.
 template <int D, bool BF16, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void kv_loop(TileState<D>& st, const char* Kh, const char* Vh, int N, float c,
-                                        int j0, int step, int it_begin, int it_end, int n_total, int qw0,
-                                        int qrow, bool wave_has_rows, const TileMap<D>& tm, int wave, int lane,
-                                        LDS_PTR(char) lds) {
+__device__ __forceinline__ void kv_loop(TileState<D>& st, ReadAddr<D>& ra, const LaneMap<D>& lm, const char* Kh,
+                                        const char* Vh, int N, float c, int j0, int step, int it_begin, int it_end,
+                                        int n_total, int qw0, int qrow, bool wave_has_rows, int lane, LDS_PTR(char) lds) {
     using G = Geo<D>;
+    const unsigned lds0 = (unsigned)(size_t)lds;
     u4 vreg[G::kLoadsPerWave];   // only used for bfloat16 inputs
+#pragma unroll 1
     for (int it = it_begin; it < it_end; ++it) {
         const int cur = it & 1;
         const int j = j0 + it * step;
-        const int kv0 = j * kTileKV;
         const bool more = it + 1 < n_total;
         if (more) {
-            tile_to_lds<D>(Kh, (j + step) * kTileKV, N, tm, wave, lds + (cur ^ 1) * G::kTile);
-            if constexpr (BF16) tile_to_regs<D>(Vh, (j + step) * kTileKV, N, tm, vreg);
-            else tile_to_lds<D>(Vh, (j + step) * kTileKV, N, tm, wave, lds + (2 + (cur ^ 1)) * G::kTile);
+            unsigned off[G::kLoadsPerWave];
+            tile_offsets<D>(j + step, N, lm, off);
+            tile_to_lds<D>(Kh, j + step, off, lm, lds0 + (cur ^ 1) * G::kTile);
+            if constexpr (BF16) tile_to_regs<D>(Vh, j + step, off, vreg);
+            else tile_to_lds<D>(Vh, j + step, off, lm, lds0 + (2 + (cur ^ 1)) * G::kTile);
         }
+        const int kv0 = j * kTileKV;
         const bool active = wave_has_rows && (!CAUSAL || kv0 <= qw0 + 31);
-        if (active)
-            compute_tile<D, BF16, CAUSAL, MASKED>(lds + cur * G::kTile, lds + (2 + cur) * G::kTile, st.qf, st.o, st.M,
-                                                  st.L, c, kv0, qrow, lane, N);
+        if (active) compute_tile<D, BF16, CAUSAL, MASKED>(st, ra, c, kv0, qrow, lane, N);
+        ra.flip(cur ? -G::kTile : G::kTile);
         if (more) {
-            if constexpr (BF16) regs_to_lds_f16<D>(vreg, wave, lane, lds + (2 + (cur ^ 1)) * G::kTile);
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
+            if constexpr (BF16) regs_to_lds_f16<D>(vreg, lm, lane, lds + (2 + (cur ^ 1)) * G::kTile);
+            wait_tile_landed();
         }
         __syncthreads();
     }
@@ -351,12 +411,11 @@ __device__ __forceinline__ void kv_loop(TileState<D>& st, const char* Kh, const 
 
 // One query tile (Alg. 1 body): rows [t*128, t*128+128) of head `hh`, K/V tiles j0, j0+step, ... (nkv of them).
 template <int D, bool BF16, bool CAUSAL>
-__device__ __forceinline__ void process_q_tile(const Params& p, int hh, int t, int j0, int step, int nkv, LDS_PTR(char) lds) {
+__device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>& lm, int hh, int t, int j0, int step,
+                                               int nkv, int wave, int lane, LDS_PTR(char) lds) {
     using G = Geo<D>;
     constexpr int KS = D / 16;    // MFMA steps along d for S^T
     constexpr int DB = D / 32;    // 32-row blocks of O^T
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int g = lane >> 5, ln = lane & 31;
     const int N = p.N;
     const size_t head_off = (size_t)hh * N * G::kRowBytes;
@@ -387,19 +446,30 @@ __device__ __forceinline__ void process_q_tile(const Params& p, int hh, int t, i
     st.M = -INFINITY;
     st.L = 0.f;
     const float c = p.c;
-    const TileMap<D> tm(wave, lane);
+    const unsigned lds0 = (unsigned)(size_t)lds;
 
-    // first tile
-    tile_to_lds<D>(Kh, j0 * kTileKV, N, tm, wave, lds);
-    if constexpr (BF16) {
-        u4 vreg[G::kLoadsPerWave];
-        tile_to_regs<D>(Vh, j0 * kTileKV, N, tm, vreg);
-        regs_to_lds_f16<D>(vreg, wave, lane, lds + 2 * G::kTile);
-    } else {
-        tile_to_lds<D>(Vh, j0 * kTileKV, N, tm, wave, lds + 2 * G::kTile);
+    // LDS: K buffers at 0 and kTile, V buffers at 2*kTile and 3*kTile.  Start on pair 0.
+    ReadAddr<D> ra;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ra.k[ks] = lds0 + lm.k_rd[ks];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) { ra.v[db][0] = lds0 + 2 * G::kTile + lm.v_rd[db][0]; ra.v[db][1] = lds0 + 2 * G::kTile + lm.v_rd[db][1]; }
+
+    // first tile into pair 0
+    {
+        unsigned off[G::kLoadsPerWave];
+        tile_offsets<D>(j0, N, lm, off);
+        tile_to_lds<D>(Kh, j0, off, lm, lds0);
+        if constexpr (BF16) {
+            u4 vreg[G::kLoadsPerWave];
+            tile_to_regs<D>(Vh, j0, off, vreg);
+            regs_to_lds_f16<D>(vreg, lm, lane, lds + 2 * G::kTile);
+        } else {
+            tile_to_lds<D>(Vh, j0, off, lm, lds0 + 2 * G::kTile);
+        }
+        wait_tile_landed();
+        __syncthreads();
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
     // the tiles that reach past the first row of this query tile.  They sit at one end of the scan.
@@ -408,11 +478,11 @@ __device__ __forceinline__ void process_q_tile(const Params& p, int hh, int t, i
     const int n_masked = nkv > jm ? nkv - jm : 0;
     const int n_plain = nkv - n_masked;
     if (step > 0) {
-        kv_loop<D, BF16, CAUSAL, false>(st, Kh, Vh, N, c, j0, step, 0, n_plain, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
-        kv_loop<D, BF16, CAUSAL, true>(st, Kh, Vh, N, c, j0, step, n_plain, nkv, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
+        kv_loop<D, BF16, CAUSAL, false>(st, ra, lm, Kh, Vh, N, c, j0, step, 0, n_plain, nkv, qw0, qrow, wave_has_rows, lane, lds);
+        kv_loop<D, BF16, CAUSAL, true>(st, ra, lm, Kh, Vh, N, c, j0, step, n_plain, nkv, nkv, qw0, qrow, wave_has_rows, lane, lds);
     } else {
-        kv_loop<D, BF16, CAUSAL, true>(st, Kh, Vh, N, c, j0, step, 0, n_masked, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
-        kv_loop<D, BF16, CAUSAL, false>(st, Kh, Vh, N, c, j0, step, n_masked, nkv, nkv, qw0, qrow, wave_has_rows, tm, wave, lane, lds);
+        kv_loop<D, BF16, CAUSAL, true>(st, ra, lm, Kh, Vh, N, c, j0, step, 0, n_masked, nkv, qw0, qrow, wave_has_rows, lane, lds);
+        kv_loop<D, BF16, CAUSAL, false>(st, ra, lm, Kh, Vh, N, c, j0, step, n_masked, nkv, nkv, qw0, qrow, wave_has_rows, lane, lds);
     }
 
     // ---- epilogue: O_i = acc / l  (the division Alg. 1 leaves implicit; Eq. 1 fixes it)
@@ -441,6 +511,9 @@ template <int D, bool BF16, bool CAUSAL>
 __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
     extern __shared__ __align__(16) char smem[];
     const Schedule& s = p.sched;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const LaneMap<D> lm(wave, lane);
     const int domain = blockIdx.x % kDomains;
     const int slot = blockIdx.x / kDomains;
     int round_counter = 0;   // rounds this domain has started (same value in all its workgroups)
@@ -458,7 +531,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
                 int32_t* rec = p.trace + ((size_t)blockIdx.x * p.max_local + local) * 4;
                 rec[0] = hh; rec[1] = t; rec[2] = j0; rec[3] = j0 + (nkv - 1) * step;
             }
-            process_q_tile<D, BF16, CAUSAL>(p, hh, t, j0, step, nkv, (LDS_PTR(char))smem);
+            process_q_tile<D, BF16, CAUSAL>(p, lm, hh, t, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
             ++local;
         }
     }
