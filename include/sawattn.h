@@ -26,7 +26,7 @@ enum {
 /* Order in which a workgroup walks the K/V tiles of one query tile (paper Sec. 4, Alg. 4). */
 enum {
     SAWATTN_SCAN_CYCLIC = 0,       /* always ascending */
-    SAWATTN_SCAN_SAWTOOTH = 1      /* ascending on even rounds, descending on odd rounds */
+    SAWATTN_SCAN_SAWTOOTH = 1      /* ascending on even, descending on odd rounds over one head's K/V */
 };
 
 enum {
@@ -100,6 +100,18 @@ int attn_fwd_trace(const void* Q, const void* K, const void* V, void* O,
                    int B, int H, int N, int d, float scale, int causal, int scan_order,
                    int in_dtype, int o_dtype, void* hip_stream,
                    int32_t* trace, int32_t* trace_count);
+
+/*
+ * attn_fwd_plan -- the schedule attn_fwd would run, computed on the host from the same work decode
+ * the kernel uses (paper Sec. 2.2 Alg. 2, Sec. 4 Alg. 4).  Launches nothing and needs no GPU.
+ *
+ *   trace        host, written: int32 [grid][max_local_tiles][4], same record layout as
+ *                attn_fwd_trace; unused records are left untouched.
+ *   trace_count  host, written: int32 [grid].
+ * B, H, N, d, causal, scan_order are validated like attn_fwd.
+ */
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order,
+                  int32_t* trace, int32_t* trace_count);
 
 /* Text of the last error raised on the calling thread ("" if none).  Static storage, never NULL. */
 const char* sawattn_last_error(void);

@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.attn_fwd_trace.argtypes = L.attn_fwd.argtypes + [vp, vp]
         L.attn_fwd_launch_info.restype = ci
         L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(LaunchInfo)]
+        L.attn_fwd_plan.restype = ci
+        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ci, ci, vp, vp]
         L.sawattn_last_error.restype = ctypes.c_char_p
         L.sawattn_last_error.argtypes = []
         L.sawattn_version.restype = ci
@@ -80,6 +82,16 @@ def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False) -
     info = LaunchInfo()
     _check(lib().attn_fwd_launch_info(B, H, N, d, int(bool(causal)), ctypes.byref(info)))
     return info.as_dict()
+
+
+def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_order="sawtooth"):
+    """Host-side schedule: returns (trace[grid, max_local, 4], count[grid]) as CPU int32 tensors."""
+    info = attn_fwd_launch_info(B, H, N, d, causal)
+    trace = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32)
+    count = torch.zeros((info["grid"],), dtype=torch.int32)
+    _check(lib().attn_fwd_plan(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order],
+                               trace.data_ptr(), count.data_ptr()))
+    return trace, count
 
 
 def _marshal(Q, K, V, O, o_dtype):

@@ -834,15 +834,14 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int domain = blockIdx.x % kDomains;
     const int slot = blockIdx.x / kDomains;
-    int round_counter = 0;   // rounds this domain has started (same value in all its workgroups)
-    int local = 0;           // query tiles this workgroup has processed (Alg. 4's i_local)
+    int local = 0;           // query tiles this workgroup has processed
     for (int cs = 0; cs < s.chunks_per_domain; ++cs) {
-        for (int r = 0; r < s.rounds_per_chunk; ++r, ++round_counter) {
+        for (int r = 0; r < s.rounds_per_chunk; ++r) {
             int hh;
             const int t = decode_tile(s, domain, slot, cs, r, CAUSAL, &hh);
             if (t < 0) continue;
             const int nkv = visible_kv_tiles(s, t, p.N, CAUSAL);
-            const bool backward = p.sawtooth && (round_counter & 1);
+            const bool backward = p.sawtooth && (r & 1);
             const int j0 = backward ? nkv - 1 : 0;
             const int step = backward ? -1 : 1;
             if (p.trace && threadIdx.x == 0) {
@@ -981,6 +980,36 @@ int attn_fwd_launch_info(int B, int H, int N, int d, int causal, sawattn_launch_
     int rc = sawattn::check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     sawattn::fill_info(sawattn::make_schedule(B * H, N), d, out);
+    return SAWATTN_OK;
+}
+
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int32_t* trace, int32_t* trace_count) {
+    using namespace sawattn;
+    if (!trace || !trace_count) return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be non-null");
+    if (scan_order != SAWATTN_SCAN_CYCLIC && scan_order != SAWATTN_SCAN_SAWTOOTH)
+        return fail(SAWATTN_ERR_INVALID_ARG, "scan_order must be SAWATTN_SCAN_CYCLIC or SAWATTN_SCAN_SAWTOOTH");
+    int rc = check_shape(B, H, N, d);
+    if (rc != SAWATTN_OK) return rc;
+    const Schedule s = make_schedule(B * H, N);
+    const int grid = kDomains * s.slots, max_local = s.chunks_per_domain * s.rounds_per_chunk;
+    // the kernel's outer loops, one workgroup at a time
+    for (int wg = 0; wg < grid; ++wg) {
+        const int domain = wg % kDomains, slot = wg / kDomains;
+        int local = 0;
+        for (int cs = 0; cs < s.chunks_per_domain; ++cs) {
+            for (int r = 0; r < s.rounds_per_chunk; ++r) {
+                int hh;
+                const int t = decode_tile(s, domain, slot, cs, r, causal != 0, &hh);
+                if (t < 0) continue;
+                const int nkv = visible_kv_tiles(s, t, N, causal != 0);
+                const bool backward = scan_order == SAWATTN_SCAN_SAWTOOTH && (r & 1);
+                int32_t* rec = trace + ((size_t)wg * max_local + local) * 4;
+                rec[0] = hh; rec[1] = t; rec[2] = backward ? nkv - 1 : 0; rec[3] = backward ? 0 : nkv - 1;
+                ++local;
+            }
+        }
+        trace_count[wg] = local;
+    }
     return SAWATTN_OK;
 }
 

@@ -14,9 +14,12 @@
 //     consecutive tiles, so all of them stream the same head's K/V at the same time;
 //   * odd rounds hand the tiles out in reverse slot order, which evens out the causal cost
 //     (tile i costs i+1 K/V tiles), and causal chunks start from their longest tile;
-//   * the scan direction of a round is the parity of the domain's round counter: this is Alg. 4's
-//     local-iteration parity for a workgroup that has a tile in every round, and keeps the whole
-//     domain walking in one direction when some workgroup sits a round out.
+//   * the scan direction of a round is the parity of the round index inside its chunk: this is
+//     Alg. 4's local-iteration parity restarted at every chunk.  Consecutive rounds of one chunk
+//     walk the same K/V, which is where reversing the direction shortens the reuse distance; the
+//     first round of a new chunk meets cold K/V whichever way it walks, and walks forward so that
+//     causal tiles all start from key 0 together.  Taking the round index rather than a per-
+//     workgroup count keeps the whole domain walking one way when a workgroup sits a round out.
 #pragma once
 
 #if defined(__HIPCC__)

@@ -1,0 +1,152 @@
+"""CPU-only tests of the host side: the C ABI surface, argument validation, the work decode /
+scan-direction schedule against its oracle, and the traffic model against the paper's counters."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import schedule_oracle as so
+from paper_2601_16032_amd import binding, traffic_model
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def sa():
+    binding.lib()
+    return binding
+
+
+# ------------------------------------------------------------------ C ABI surface
+def test_library_exports_every_declared_symbol(sa):
+    header = open(os.path.join(ROOT, "include", "sawattn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", header)
+    assert set(names) >= {"attn_fwd", "attn_fwd_trace", "attn_fwd_launch_info", "attn_fwd_plan",
+                          "sawattn_last_error", "sawattn_version"}
+    L = sa.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in sawattn.h but not exported"
+    assert sa.sawattn_version() >= 100
+
+
+def test_argument_validation_without_a_gpu(sa):
+    """Every case below is rejected before anything is launched, so fake pointers are safe."""
+    L = sa.lib()
+    ok_ptr = 0x1000
+    base = dict(Q=ok_ptr, K=ok_ptr, V=ok_ptr, O=ok_ptr, B=1, H=1, N=128, d=64, scale=0.125, causal=0,
+                scan=1, idt=0, odt=0)
+
+    def call(**kw):
+        a = dict(base, **kw)
+        return L.attn_fwd(a["Q"], a["K"], a["V"], a["O"], a["B"], a["H"], a["N"], a["d"], a["scale"],
+                          a["causal"], a["scan"], a["idt"], a["odt"], None)
+
+    assert call(Q=None) == binding.ERR_INVALID_ARG
+    assert call(O=None) == binding.ERR_INVALID_ARG
+    assert call(K=ok_ptr + 8) == binding.ERR_INVALID_ARG          # misaligned
+    assert "aligned" in sa.sawattn_last_error()
+    assert call(B=0) == binding.ERR_INVALID_ARG
+    assert call(N=-5) == binding.ERR_INVALID_ARG
+    assert call(d=96) == binding.ERR_UNSUPPORTED
+    assert "64 or 128" in sa.sawattn_last_error()
+    assert call(scale=float("nan")) == binding.ERR_INVALID_ARG
+    assert call(scale=float("inf")) == binding.ERR_INVALID_ARG
+    assert call(scan=2) == binding.ERR_INVALID_ARG
+    assert call(idt=2) == binding.ERR_INVALID_ARG                 # fp32 inputs are not accepted
+    assert call(odt=3) == binding.ERR_INVALID_ARG
+    assert call(B=1 << 20, H=1 << 10, N=1 << 20) == binding.ERR_INVALID_ARG   # size overflow
+    with pytest.raises(binding.SawattnError):
+        sa.attn_fwd_launch_info(1, 1, 128, 80)
+
+
+# ------------------------------------------------------------------ schedule oracle: what must hold
+SHAPES = [(1, 1, 256), (1, 8, 2048), (1, 16, 8192), (1, 32, 16384), (4, 32, 32768), (2, 3, 333),
+          (1, 12, 1000), (3, 7, 300), (1, 8, 128 * 70), (1, 2, 1), (5, 1, 129), (1, 64, 100)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N", SHAPES)
+def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
+    sched = so.schedule(B, H, N, causal, "sawtooth")
+    geo = so.launch_geometry(B, H, N)
+    seen = {}
+    for wg, recs in sched.items():
+        for (head, t, first, last) in recs:
+            assert (head, t) not in seen
+            seen[(head, t)] = wg
+            n_kv = -(-min((t + 1) * 128, N) // 64) if causal else -(-N // 64)
+            assert {first, last} == {0, n_kv - 1}             # the whole visible range, one direction
+    assert set(seen) == {(h, t) for h in range(B * H) for t in range(geo["q_tiles"])}
+    # a head's tiles stay inside the domains it is assigned to, and workgroups of one domain that
+    # work in the same round walk in the same direction
+    for (head, t), wg in seen.items():
+        part = t % geo["parts"]
+        assert wg % 8 == (head * geo["parts"] + part) % 8
+    cyc = so.schedule(B, H, N, causal, "cyclic")
+    for wg in sched:
+        assert [r[:2] for r in cyc[wg]] == [r[:2] for r in sched[wg]]   # same tiles, only direction differs
+        assert all(r[2] == 0 for r in cyc[wg])
+
+
+def test_schedule_oracle_hand_example():
+    """B*H = 8, N = 128*130: one head per domain, 64 slots, 3 rounds (64 + 64 + 2 tiles).
+    Slot 5 of domain 3: round 0 -> tile 5 forward; round 1 (reverse hand-out) -> tile 64 + 58
+    backward; round 2 (2 tiles, forward hand-out) -> nothing."""
+    s = so.schedule(1, 8, 128 * 130, False, "sawtooth")
+    n_kv = 128 * 130 // 64
+    assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 64 + 58, n_kv - 1, 0)]
+    assert s[1 * 8 + 3] == [(3, 1, 0, n_kv - 1), (3, 64 + 62, n_kv - 1, 0), (3, 129, 0, n_kv - 1)]
+
+
+# ------------------------------------------------------------------ host plan == oracle
+@pytest.mark.parametrize("order", ["cyclic", "sawtooth"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N", SHAPES)
+def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
+    info = sa.attn_fwd_launch_info(B, H, N, 128, causal)
+    geo = so.launch_geometry(B, H, N)
+    assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
+    assert info["parts_per_head"] == geo["parts"] and info["q_tiles_per_head"] == geo["q_tiles"]
+    trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, order)
+    want = so.schedule(B, H, N, causal, order)
+    for wg in range(info["grid"]):
+        got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
+        assert got == want[wg], f"workgroup {wg}"
+
+
+# ------------------------------------------------------------------ traffic model vs the paper's counters
+def test_sector_model_matches_printed_counters():
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "l2_sector_counters.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 4
+    for table, S, total, from_tex in rows:
+        model = traffic_model.l2_sectors_noncausal(int(S), T=80)
+        assert abs(model - int(total)) / int(total) < 0.01        # Table 3: mean error 0.45 %
+        assert abs(model - int(from_tex)) / int(from_tex) < 0.01
+    # the closed forms the paper prints for D=64, fp16, 32-byte sectors
+    S, T = 4096, 64
+    assert traffic_model.l2_sectors_noncausal(S, T) == pytest.approx(8 * S * (1 + S / T))
+    assert traffic_model.l2_sectors_causal(S, T) == pytest.approx(8 * S * (S / (2 * T) + 0.5))
+    assert traffic_model.cold_miss_sectors(S) == 16 * S
+
+
+def test_byte_model_and_lru_model():
+    # workload 4: Q + 128 passes over K,V per head
+    b = traffic_model.l2_read_bytes(1, 32, 16384, 128, 128, False)
+    assert b == 32 * (16384 * 128 * 2) * (1 + 2 * 128)
+    assert traffic_model.l2_read_bytes(1, 1, 1024, 64, 128, True) == 1024 * 64 * 2 * (1 + 2 * 9 / 2)
+    assert traffic_model.compulsory_bytes(1, 32, 16384, 128) == 512 * 2 ** 20
+    kv = 2 * 16384 * 128 * 2
+    assert traffic_model.lru_kv_miss_bytes(16384, 128, 128, 64, 4 * 2 ** 20, False) == 2 * kv
+    assert traffic_model.lru_kv_miss_bytes(16384, 128, 128, 64, 4 * 2 ** 20, True) == 2 * kv - 4 * 2 ** 20
+    assert traffic_model.lru_kv_miss_bytes(2048, 64, 128, 16, 4 * 2 ** 20, False) == 2 * 2048 * 64 * 2
+    # the paper's high-level-kernel experiment (Sec. 4.3): batch 8, S = 128K, D = 64, tile 64,
+    # 48 lock-stepped workgroups on a 24 MiB L2: cyclic misses ~ all-access sectors / 48 ~ 3.6e8,
+    # reported ~3.7e8; sawtooth reported ~1.2e8
+    S = 131072
+    all_access = 8 * traffic_model.l2_sectors_noncausal(S, 64)
+    assert all_access / 48 == pytest.approx(3.7e8, rel=0.05)
