@@ -94,6 +94,7 @@ def cpu_baseline(w, Q, K, V, target_seconds):
         return dt, fl
 
     n0 = min(w.N, 256)
+    run(0, 0, 16)                                  # first call loads the library and starts the threads
     dt0, fl0 = run(0, 0, n0)                       # calibration, not counted
     rows_budget = int(n0 * target_seconds / max(dt0, 1e-4))
     total_dt = total_fl = 0.0
