@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--scan-order", default="both", choices=["both", "sawtooth", "cyclic"],
                     help="'both' times sawtooth (the headline) and cyclic; a single order is for profiling")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (reference reading for FETCH_SIZE / WRITE_SIZE)")
@@ -75,6 +76,22 @@ def time_order(sa, torch, Q, K, V, O, w, order, steps, warmup, evict_buf=None):
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     kernel_ms = sum(a.elapsed_time(b) for a, b in zip(starts, stops)) / steps
     return wall_ms, kernel_ms
+
+
+def mfma_probe(sa, torch):
+    """Matrix rate this chip sustains (context for roofline.frac, which uses the datasheet peak)."""
+    res = {"unit": "TFLOP/s"}
+    for mode, key in ((0, "registers_fixed_operands"), (1, "lds_fed_random_operands")):
+        for _ in range(2):
+            sa.sawattn_mfma_probe(2000, mode)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = sum(sa.sawattn_mfma_probe(4000, mode) for _ in range(5))
+        e1.record()
+        torch.cuda.synchronize()
+        res[key] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return res
 
 
 def cpu_baseline(w, Q, K, V, target_seconds):
@@ -176,6 +193,8 @@ def main():
         "scan_orders": {o: {"tflops": res[o]["tflops"], "kernel_ms": res[o]["kernel_ms"],
                             "tcc_miss": MEASURED_TCC_MISS.get((args.workload, o))} for o in orders},
     }
+    if not args.no_mfma_probe:
+        out["mfma_probe"] = mfma_probe(sa, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, Q, K, V, args.cpu_seconds)
     print(json.dumps(out))

@@ -113,6 +113,21 @@ int attn_fwd_trace(const void* Q, const void* K, const void* V, void* O,
 int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order,
                   int32_t* trace, int32_t* trace_count);
 
+/*
+ * sawattn_mfma_probe -- measurement aid for the roofline (paper Sec. 4.2 / 4.3 report throughput;
+ * this gives the matrix rate the chip sustains, next to which the attention rate is read).  Launches
+ * one 8-wavefront workgroup per compute unit; each wavefront issues iters*16 v_mfma_f32_32x32x16_f16.
+ *
+ *   sink       device, >= 512 floats; never written in practice (keeps the work alive).
+ *   iters      > 0.
+ *   mode       0: operands fixed in registers;  1: A operands re-read from an LDS tile of
+ *              pseudo-random values with the attention kernel's K-operand pattern.
+ *   hip_stream stream to launch on (NULL = default); returns without waiting.
+ *   flops_out  host, optional: receives the flop count of the launch (2*32*32*16 per MFMA).
+ * Errors: INVALID_ARG, RUNTIME.
+ */
+int sawattn_mfma_probe(float* sink, int iters, int mode, void* hip_stream, double* flops_out);
+
 /* Text of the last error raised on the calling thread ("" if none).  Static storage, never NULL. */
 const char* sawattn_last_error(void);
 

@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_plan.restype = ci
         L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ci, ci, vp, vp]
+        L.sawattn_mfma_probe.restype = ci
+        L.sawattn_mfma_probe.argtypes = [vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
         L.sawattn_last_error.restype = ctypes.c_char_p
         L.sawattn_last_error.argtypes = []
         L.sawattn_version.restype = ci
@@ -92,6 +94,15 @@ def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_ord
     _check(lib().attn_fwd_plan(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order],
                                trace.data_ptr(), count.data_ptr()))
     return trace, count
+
+
+def sawattn_mfma_probe(iters: int, mode: int, stream=None) -> float:
+    """Enqueue the matrix-rate probe on the current (or given) stream; returns its flop count."""
+    sink = torch.zeros(512, dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    st = stream if stream is not None else torch.cuda.current_stream()
+    _check(lib().sawattn_mfma_probe(sink.data_ptr(), int(iters), int(mode), st.cuda_stream, ctypes.byref(flops)))
+    return float(flops.value)
 
 
 def _marshal(Q, K, V, O, o_dtype):

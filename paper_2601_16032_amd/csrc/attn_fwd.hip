@@ -865,6 +865,58 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
     if (p.trace_count && threadIdx.x == 0) p.trace_count[blockIdx.x] = local;
 }
 
+
+// ------------------------------------------------------------------------------- sustained-rate probe
+// What the matrix pipes of this chip sustain, to put the datasheet peak into context: every
+// wavefront runs `iters` x 16 v_mfma_f32_32x32x16_f16 on four independent accumulators.
+//   mode 0: operands fixed in registers (least switching activity, highest clock);
+//   mode 1: A operands re-read from an LDS tile of pseudo-random binary16 values with the K-operand
+//           access pattern of the attention kernel, one ds_read_b128 per MFMA: the best any kernel
+//           that feeds 32-row operands from LDS with live data can reach.
+// The chip lowers its clock with matrix activity, so the two differ markedly.
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters, int mode) {
+    __shared__ __align__(16) char tile[16384];
+    LDS_PTR(char) lds = (LDS_PTR(char))tile;
+    for (int i = threadIdx.x; i < 16384 / 4; i += blockDim.x) {
+        const unsigned hsh = (i * 2654435761u) ^ ((i >> 3) * 40503u);
+        ((LDS_PTR(unsigned))lds)[i] = (hsh & 0x83ff83ffu) | 0x38003800u;   // binary16 pairs with |x| in [0.5, 1)
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, g = lane >> 5, ln = lane & 31;
+    u4 b;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) b[e] = 0x38003c00u + ((threadIdx.x * 37u + e * 11u) % 97u) * 0x00010003u;
+    f16v c[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) c[q][r] = 0.f;
+    unsigned addr[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) addr[ks] = (unsigned)(size_t)lds + ln * 256 + ((2 * ks + g) ^ Geo<128>::swz(ln)) * 16;
+    if (mode == 0) {
+        const u4 a = *(LDS_PTR(u4))(size_t)addr[0];
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int t = 0; t < 16; ++t) c[t & 3] = mfma_16bit<false>(a, b, c[t & 3]);
+        }
+    } else {
+        for (int i = 0; i < iters; ++i) {
+            u4 a[16];
+            a[0] = *(LDS_PTR(u4))(size_t)addr[0];
+            a[1] = *(LDS_PTR(u4))(size_t)(addr[0] + 8192);
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                if (t + 2 < 16) a[t + 2] = *(LDS_PTR(u4))(size_t)(addr[(t + 2) / 2] + ((t + 2) & 1) * 8192);
+                c[t & 3] = mfma_16bit<false>(a[t], b, c[t & 3]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+    const float res = c[0][0] + c[1][1] + c[2][2] + c[3][3];
+    if (res == 123.456f) sink[threadIdx.x] = res;   // never true: keeps the accumulators alive
+}
+
 // ------------------------------------------------------------------------------------------- host
 
 thread_local char g_err[256] = "";
@@ -1010,6 +1062,20 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int32_
         }
         trace_count[wg] = local;
     }
+    return SAWATTN_OK;
+}
+
+int sawattn_mfma_probe(float* sink, int iters, int mode, void* hip_stream, double* flops_out) {
+    using namespace sawattn;
+    if (!sink || iters <= 0 || (mode != 0 && mode != 1)) return fail(SAWATTN_ERR_INVALID_ARG, "sink non-null, iters > 0, mode 0 or 1");
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(SAWATTN_ERR_RUNTIME, "cannot query the device");
+    }
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(cus), dim3(512), 0, static_cast<hipStream_t>(hip_stream), sink, iters, mode);
+    if (hipGetLastError() != hipSuccess) return fail(SAWATTN_ERR_RUNTIME, "probe launch failed");
+    if (flops_out) *flops_out = (double)cus * 8.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
     return SAWATTN_OK;
 }
 
