@@ -376,21 +376,42 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
     }
 }
 
-// K/V iterations [it_begin, it_end) of one query tile, all with or all without the mask code.
-// Iteration `it` uses tile j0 + it*step out of LDS buffer pair it & 1 and, while computing,
-// fetches the tile of iteration it+1 (if it + 1 < n_total) into the other pair.
+// A run of `count` K/V tiles j_first, j_first + step, ... processed one tile at a time (all with or
+// all without the mask code).  Self-contained: fetches its first tile itself and leaves with every
+// wavefront past the barrier that follows its last tile.  Iteration `it` uses LDS buffer pair it & 1
+// and, while computing, fetches the tile of iteration it+1 into the other pair.
 template <int D, bool BF16, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void kv_loop(TileState<D>& st, ReadAddr<D>& ra, const LaneMap<D>& lm, const char* Kh,
-                                        const char* Vh, int N, float c, int j0, int step, int it_begin, int it_end,
-                                        int n_total, int qw0, int qrow, bool wave_has_rows, int lane, LDS_PTR(char) lds) {
+__device__ __forceinline__ void general_range(TileState<D>& st, const LaneMap<D>& lm, const char* Kh, const char* Vh, int N,
+                                              float c, int j_first, int step, int count, int qw0, int qrow,
+                                              bool wave_has_rows, int lane, LDS_PTR(char) lds) {
     using G = Geo<D>;
+    if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
     u4 vreg[G::kLoadsPerWave];   // only used for bfloat16 inputs
+    // LDS: K buffers at 0 and kTile, V buffers at 2*kTile and 3*kTile.  Start on pair 0.
+    ReadAddr<D> ra;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) ra.k[ks] = lds0 + lm.k_rd[ks];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) { ra.v[db][0] = lds0 + 2 * G::kTile + lm.v_rd[db][0]; ra.v[db][1] = lds0 + 2 * G::kTile + lm.v_rd[db][1]; }
+    {
+        unsigned off[G::kLoadsPerWave];
+        tile_offsets<D>(j_first, N, lm, off);
+        tile_to_lds<D>(Kh, j_first, off, lm, lds0);
+        if constexpr (BF16) {
+            tile_to_regs<D>(Vh, j_first, off, vreg);
+            regs_to_lds_f16<D>(vreg, lm, lane, lds + 2 * G::kTile);
+        } else {
+            tile_to_lds<D>(Vh, j_first, off, lm, lds0 + 2 * G::kTile);
+        }
+        wait_tile_landed();
+        __syncthreads();
+    }
 #pragma unroll 1
-    for (int it = it_begin; it < it_end; ++it) {
+    for (int it = 0; it < count; ++it) {
         const int cur = it & 1;
-        const int j = j0 + it * step;
-        const bool more = it + 1 < n_total;
+        const int j = j_first + it * step;
+        const bool more = it + 1 < count;
         if (more) {
             unsigned off[G::kLoadsPerWave];
             tile_offsets<D>(j + step, N, lm, off);
@@ -408,6 +429,265 @@ __device__ __forceinline__ void kv_loop(TileState<D>& st, ReadAddr<D>& ra, const
         }
         __syncthreads();
     }
+}
+
+// A run of `count` full, unmasked K/V tiles j_first, j_first + step, ..., software pipelined across
+// tiles.  While the MFMAs of S(i+1)^T = K(i+1) Q^T run, the exponentials of tile i are issued
+// between them; while the MFMAs of O^T += V(i)^T P(i)^T run, the row maximum of S(i+1), the
+// lazy-rescale check and the (score*c - M) of tile i+1 are issued between them.  Two register sets
+// alternate roles without copies: `A` accumulates the scores of the tile one ahead, `x` holds the
+// shifted scores of the current tile until they have become probabilities.  K is therefore fetched
+// two tiles ahead and V one tile ahead, still into two LDS buffers each.  For bfloat16 inputs V
+// travels global -> registers -> binary16 -> LDS, the conversion spread over the second product.
+// Self-contained like general_range().
+template <int D, bool BF16>
+__device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<D>& lm, const char* Kh, const char* Vh,
+                                                float c, int j_first, int step, int count, int lane, LDS_PTR(char) lds) {
+    using G = Geo<D>;
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int NA = 2 * KS;            // MFMAs of one S^T tile
+    constexpr int NB = 4 * DB;            // MFMAs of one O^T update
+    constexpr int NL = G::kLoadsPerWave;
+    constexpr int EU = 16 / NA;           // exp units (2 exp + convert + sum of one pair) per MFMA of phase A
+    if (count <= 0) return;
+    const unsigned lds0 = (unsigned)(size_t)lds;
+    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    const f16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f16v A[2];          // S^T of the tile one ahead: block b = keys 32b..32b+31 of the tile
+    float x[32];        // score*c - M of the current tile, index 16*b + r
+    u4 pf[4];           // its probabilities as B operands
+    u4 vreg[NL];        // bfloat16 V chunks in flight (BF16 only)
+
+    // LDS read addresses: K of the tile one ahead, V of the current tile
+    unsigned rk[KS], rv[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) rk[ks] = lds0 + lm.k_rd[ks];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) { rv[db][0] = lds0 + 2 * G::kTile + lm.v_rd[db][0]; rv[db][1] = lds0 + 2 * G::kTile + lm.v_rd[db][1]; }
+
+    auto tile_base = [&](const char* head, int i) { return head + (size_t)(j_first + i * step) * kTileKV * G::kRowBytes; };
+    auto fetch_burst = [&](const char* head, int i, unsigned dst) {
+        const char* base = tile_base(head, i);
+#pragma unroll
+        for (int l = 0; l < NL; ++l) load_to_lds_16B(base, lm.fill_src[l], dst + lm.fill_dst + l * 4096);
+    };
+    auto k_read = [&](int m) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[m / 2] + (m & 1) * 32 * G::kRowBytes); };
+    auto v_read = [&](int idx) -> s8 {
+        const int ks = idx / DB, db = idx % DB;
+        const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][0] + ks * 16 * G::kRowBytes));
+        const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][1] + ks * 16 * G::kRowBytes));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    auto rescale = [&](float tmax) {
+        const float Mnew = fmaxf(st.M, tmax);
+        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st.M - Mnew);
+        st.M = Mnew;
+        st.L *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;
+    };
+    float tmax_ahead = 0.f;   // row maximum (times c) of the tile in A, from the latest iteration
+    // exp unit u (0..15): the two exponentials of pair u, and the convert + sum of pair u-1
+    float e0[16], e1[16];
+    auto exp_unit = [&](int u) {
+        if (u < 16) {
+            e0[u] = fast_exp2(x[2 * u]);
+            e1[u] = fast_exp2(x[2 * u + 1]);
+        }
+        if (u >= 1 && u <= 16) {
+            const int v = u - 1;
+            const h2 ph = __builtin_convertvector(f2{e0[v], e1[v]}, h2);
+            st.L = __builtin_amdgcn_fdot2(ph, ones, st.L, false);   // sum of the rounded probabilities
+            pf[v / 4][v % 4] = __builtin_bit_cast(unsigned, ph);
+        }
+    };
+
+    // ---------------------------------------------------------------- prologue: tile 0
+    fetch_burst(Kh, 0, lds0);
+    if constexpr (BF16) {
+        const char* base = tile_base(Vh, 0);
+#pragma unroll
+        for (int l = 0; l < NL; ++l) vreg[l] = *reinterpret_cast<const u4*>(base + lm.fill_src[l]);
+        regs_to_lds_f16<D>(vreg, lm, lane, lds + 2 * G::kTile);
+    } else {
+        fetch_burst(Vh, 0, lds0 + 2 * G::kTile);
+    }
+    wait_tile_landed();
+    __syncthreads();
+    if (count > 1) fetch_burst(Kh, 1, lds0 + G::kTile);
+    {
+        u4 a[NA];
+        a[0] = k_read(0);
+        a[1] = k_read(1);
+#pragma unroll
+        for (int m = 0; m < NA; ++m) {
+            if (m + 2 < NA) a[m + 2] = k_read(m + 2);
+            A[m & 1] = mfma_16bit<BF16>(a[m], st.qf[m / 2], m < 2 ? zero : A[m & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        float mx = fmaxf(A[0][0], A[0][1]);
+#pragma unroll
+        for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, A[r >> 4][r & 15]), A[r >> 4][(r & 15) + 1]);
+        const float tmax = pair_max(mx) * c;
+        if (__builtin_amdgcn_ballot_w64(!(tmax <= st.M + kRescaleSlack)) != 0) rescale(tmax);
+#pragma unroll
+        for (int r = 0; r < 32; ++r) x[r] = __builtin_fmaf(A[r >> 4][r & 15], c, -st.M);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) rk[ks] += G::kTile;   // K of tile 1 is in buffer 1
+    if (count > 1) {
+        wait_tile_landed();
+        __syncthreads();
+    }
+
+    // ---------------------------------------------------------------- steady state: iteration i
+    // reads K(i+1) from K buffer (i+1)&1 and V(i) from V buffer i&1; fetches K(i+2) into K buffer
+    // i&1 and V(i+1) into V buffer (i+1)&1.  Returns whether the reference maximum has to be raised
+    // before tile i+1 can be used.
+    auto iteration = [&](int i, auto fetch_k_tag) -> bool {
+        constexpr bool FETCH_K = decltype(fetch_k_tag)::value;
+        const int cur = i & 1;
+        const char* kbase = tile_base(Kh, i + 2);
+        const char* vbase = tile_base(Vh, i + 1);
+        const unsigned kdst = lds0 + cur * G::kTile + lm.fill_dst;
+        const unsigned vdst = lds0 + (2 + (cur ^ 1)) * G::kTile + lm.fill_dst;
+        // ---- phase A
+        {
+            u4 a[NA];
+            a[0] = k_read(0);
+            a[1] = k_read(1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int m = 0; m < NA; ++m) {
+                if (m + 2 < NA) a[m + 2] = k_read(m + 2);
+                A[m & 1] = mfma_16bit<BF16>(a[m], st.qf[m / 2], m < 2 ? zero : A[m & 1]);
+#pragma unroll
+                for (int q = 0; q < EU; ++q) exp_unit(m * EU + q);
+                if ((m * 2 * NL) / NA != ((m + 1) * 2 * NL) / NA) {
+                    const int li = (m * 2 * NL) / NA;
+                    if (li < NL) {
+                        if (FETCH_K) load_to_lds_16B(kbase, lm.fill_src[li], kdst + li * 4096);
+                    } else if constexpr (BF16) {
+                        vreg[li - NL] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[li - NL]);
+                    } else {
+                        load_to_lds_16B(vbase, lm.fill_src[li - NL], vdst + (li - NL) * 4096);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            exp_unit(16);
+        }
+        // ---- phase B, first half: row maximum of A and the rescale check
+        s8 av[NB];
+        av[0] = v_read(0);
+        av[1] = v_read(1);
+        __builtin_amdgcn_sched_barrier(0);
+        float mx = 0.f;
+        constexpr int H = NB / 2;          // MFMAs before the check
+        constexpr int MS = 2;              // first slot that may read A (MFMA result latency)
+        constexpr int MPS = (16 + (H - MS) - 1) / (H - MS);   // max3 ops per slot
+#pragma unroll
+        for (int idx = 0; idx < H; ++idx) {
+            av[idx + 2] = v_read(idx + 2);
+            st.o[idx % DB] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[idx / DB]),
+                                                                    st.o[idx % DB], 0, 0, 0);
+            if (idx >= MS) {
+#pragma unroll
+                for (int q = 0; q < MPS; ++q) {
+                    const int op = (idx - MS) * MPS + q;   // op-th max3: elements 2*op, 2*op+1
+                    if (op < 16) {
+                        const float u0 = A[(2 * op) >> 4][(2 * op) & 15], u1 = A[(2 * op) >> 4][((2 * op) & 15) + 1];
+                        mx = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx, u0), u1);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        tmax_ahead = pair_max(mx) * c;
+        const bool need = __builtin_amdgcn_ballot_w64(!(tmax_ahead <= st.M + kRescaleSlack)) != 0;
+        // ---- phase B, second half, with the shifted scores of tile i+1 in between (and, for
+        //      bfloat16, the conversion of the fetched V chunks).  If the reference maximum has to
+        //      be raised (need), the shifted scores are recomputed after the loop exit.
+        constexpr int FPS = 32 / (NB - H);   // fmas per slot
+        constexpr int CPS = (NL * 4 + (NB - H) - 1) / (NB - H);   // bf16 pair conversions per slot
+#pragma unroll
+        for (int idx = H; idx < NB; ++idx) {
+            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
+            st.o[idx % DB] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[idx / DB]),
+                                                                    st.o[idx % DB], 0, 0, 0);
+#pragma unroll
+            for (int q = 0; q < FPS; ++q) {
+                const int r = (idx - H) * FPS + q;
+                x[r] = __builtin_fmaf(A[r >> 4][r & 15], c, -st.M);
+            }
+            if constexpr (BF16) {
+#pragma unroll
+                for (int q = 0; q < CPS; ++q) {
+                    const int w = (idx - H) * CPS + q;    // w-th 32-bit word of the fetched chunks
+                    if (w < NL * 4) {
+                        f2 y;
+                        y[0] = __builtin_bit_cast(float, vreg[w / 4][w % 4] << 16);
+                        y[1] = __builtin_bit_cast(float, vreg[w / 4][w % 4] & 0xffff0000u);
+                        vreg[w / 4][w % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(y, h2));
+                        if (w % 4 == 3)
+                            *(LDS_PTR(u4))(size_t)(vdst + (w / 4) * 4096 + lane * 16) = vreg[w / 4];
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- switch buffers, publish the fetched tiles
+        const int dk = cur ? G::kTile : -G::kTile;   // K(i+2) is in buffer i&1
+        const int dv = cur ? -G::kTile : G::kTile;   // V(i+1) is in buffer (i+1)&1
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) rk[ks] += dk;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) { rv[db][0] += dv; rv[db][1] += dv; }
+        wait_tile_landed();
+        __syncthreads();
+        return need;
+    };
+    // Raise the reference maximum for the tile held in A and redo its shifted scores; only reached
+    // when the loop below stopped because an iteration asked for it.
+    auto raise_reference = [&]() {
+        rescale(tmax_ahead);
+#pragma unroll
+        for (int r = 0; r < 32; ++r) x[r] = __builtin_fmaf(A[r >> 4][r & 15], c, -st.M);
+    };
+    int i = 0;
+    while (i + 2 < count) {
+        bool need = false;
+#pragma unroll 1
+        for (; i + 2 < count; ++i) {
+            need = iteration(i, std::true_type{});
+            if (need) { ++i; break; }
+        }
+        if (need) raise_reference();
+    }
+    if (i + 1 < count) {
+        const bool need = iteration(i, std::false_type{});
+        ++i;
+        if (need) raise_reference();
+    }
+
+    // ---------------------------------------------------------------- last tile: probabilities, then O^T += V^T P^T
+#pragma unroll
+    for (int u = 0; u <= 16; ++u) exp_unit(u);
+    {
+        s8 av[NB];
+        av[0] = v_read(0);
+        av[1] = v_read(1);
+#pragma unroll
+        for (int idx = 0; idx < NB; ++idx) {
+            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
+            st.o[idx % DB] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[idx / DB]),
+                                                                    st.o[idx % DB], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __syncthreads();   // all reads of the last tile are done before anything refills the buffers
 }
 
 // One query tile (Alg. 1 body): rows [t*128, t*128+128) of head `hh`, K/V tiles j0, j0+step, ... (nkv of them).
@@ -447,43 +727,20 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
     st.M = -INFINITY;
     st.L = 0.f;
     const float c = p.c;
-    const unsigned lds0 = (unsigned)(size_t)lds;
-
-    // LDS: K buffers at 0 and kTile, V buffers at 2*kTile and 3*kTile.  Start on pair 0.
-    ReadAddr<D> ra;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) ra.k[ks] = lds0 + lm.k_rd[ks];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) { ra.v[db][0] = lds0 + 2 * G::kTile + lm.v_rd[db][0]; ra.v[db][1] = lds0 + 2 * G::kTile + lm.v_rd[db][1]; }
-
-    // first tile into pair 0
-    {
-        unsigned off[G::kLoadsPerWave];
-        tile_offsets<D>(j0, N, lm, off);
-        tile_to_lds<D>(Kh, j0, off, lm, lds0);
-        if constexpr (BF16) {
-            u4 vreg[G::kLoadsPerWave];
-            tile_to_regs<D>(Vh, j0, off, vreg);
-            regs_to_lds_f16<D>(vreg, lm, lane, lds + 2 * G::kTile);
-        } else {
-            tile_to_lds<D>(Vh, j0, off, lm, lds0 + 2 * G::kTile);
-        }
-        wait_tile_landed();
-        __syncthreads();
-    }
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
-    // the tiles that reach past the first row of this query tile.  They sit at one end of the scan.
+    // the tiles that reach past the first row of this query tile.  They sit at one end of the scan,
+    // so the scan is a pipelined run of plain tiles and a run of masked tiles, in scan order.
     const int kv_tiles = (N + kTileKV - 1) / kTileKV;
     const int jm = CAUSAL ? (t * kTileQ) / kTileKV : ((N % kTileKV) ? kv_tiles - 1 : kv_tiles);
     const int n_masked = nkv > jm ? nkv - jm : 0;
     const int n_plain = nkv - n_masked;
     if (step > 0) {
-        kv_loop<D, BF16, CAUSAL, false>(st, ra, lm, Kh, Vh, N, c, j0, step, 0, n_plain, nkv, qw0, qrow, wave_has_rows, lane, lds);
-        kv_loop<D, BF16, CAUSAL, true>(st, ra, lm, Kh, Vh, N, c, j0, step, n_plain, nkv, nkv, qw0, qrow, wave_has_rows, lane, lds);
+        pipelined_range<D, BF16>(st, lm, Kh, Vh, c, j0, step, n_plain, lane, lds);
+        general_range<D, BF16, CAUSAL, true>(st, lm, Kh, Vh, N, c, j0 + n_plain * step, step, n_masked, qw0, qrow, wave_has_rows, lane, lds);
     } else {
-        kv_loop<D, BF16, CAUSAL, true>(st, ra, lm, Kh, Vh, N, c, j0, step, 0, n_masked, nkv, qw0, qrow, wave_has_rows, lane, lds);
-        kv_loop<D, BF16, CAUSAL, false>(st, ra, lm, Kh, Vh, N, c, j0, step, n_masked, nkv, nkv, qw0, qrow, wave_has_rows, lane, lds);
+        general_range<D, BF16, CAUSAL, true>(st, lm, Kh, Vh, N, c, j0, step, n_masked, qw0, qrow, wave_has_rows, lane, lds);
+        pipelined_range<D, BF16>(st, lm, Kh, Vh, c, j0 + n_masked * step, step, n_plain, lane, lds);
     }
 
     // ---- epilogue: O_i = acc / l  (the division Alg. 1 leaves implicit; Eq. 1 fixes it)
@@ -496,324 +753,6 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             for (int rq = 0; rq < 4; ++rq) {
                 const f16v& o = st.o[db];
                 f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
-                const size_t col = 32 * db + 8 * rq + 4 * g;
-                if (p.o_dtype == SAWATTN_F32) {
-                    *reinterpret_cast<f4*>(static_cast<float*>(p.O) + orow + col) = v;
-                } else if (p.o_dtype == SAWATTN_F16) {
-                    *reinterpret_cast<h4*>(static_cast<_Float16*>(p.O) + orow + col) = __builtin_convertvector(v, h4);
-                } else {
-                    *reinterpret_cast<b4*>(static_cast<__bf16*>(p.O) + orow + col) = __builtin_convertvector(v, b4);
-                }
-            }
-    }
-}
-
-// Query tile with the K/V loop software pipelined across tiles (binary16 inputs, N a multiple of
-// the K/V tile).  While the MFMAs of S(i+1)^T = K(i+1) Q^T run, the exponentials of tile i are
-// issued between them; while the MFMAs of O^T += V(i)^T P(i)^T run, the row maximum of S(i+1), the
-// lazy-rescale check and the (score*c - M) of tile i+1 are issued between them.  Two register
-// sets alternate roles without copies: `A` accumulates the scores of the tile one ahead, `x` holds
-// the shifted scores of the current tile until they have become probabilities.  K is therefore
-// fetched two tiles ahead and V one tile ahead, still into two LDS buffers each.
-template <int D, bool CAUSAL>
-__device__ __forceinline__ void process_q_tile_pipelined(const Params& p, const LaneMap<D>& lm, int hh, int t, int j0,
-                                                         int step, int nkv, int wave, int lane, LDS_PTR(char) lds) {
-    using G = Geo<D>;
-    constexpr int KS = D / 16, DB = D / 32;
-    constexpr int NA = 2 * KS;            // MFMAs of one S^T tile
-    constexpr int NB = 4 * DB;            // MFMAs of one O^T update
-    constexpr int NL = G::kLoadsPerWave;
-    constexpr int EU = 16 / NA;           // exp units (2 exp + convert + sum of one pair) per MFMA of phase A
-    const int g = lane >> 5, ln = lane & 31;
-    const int N = p.N;
-    const size_t head_off = (size_t)hh * N * G::kRowBytes;
-    const char* Qh = static_cast<const char*>(p.Q) + head_off;
-    const char* Kh = static_cast<const char*>(p.K) + head_off;
-    const char* Vh = static_cast<const char*>(p.V) + head_off;
-    const int qrow = t * kTileQ + wave * 32 + ln;   // this lane's query row (< N: N is a multiple of 64... of the tile)
-    const float c = p.c;
-    const unsigned lds0 = (unsigned)(size_t)lds;
-    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
-
-    u4 qf[KS];
-    {
-        const int qr = qrow < N ? qrow : N - 1;
-        const char* qp = Qh + (size_t)qr * G::kRowBytes + g * 16;
-        const unsigned flip = p.negate_q ? 0x80008000u : 0u;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
-            v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
-            qf[ks] = v;
-        }
-    }
-    f16v o[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
-    float M = -INFINITY, L = 0.f;
-    f16v A[2];          // S^T of the tile one ahead: block b = keys 32b..32b+31 of the tile
-    float x[32];        // score*c - M of the current tile, index 16*b + r
-    u4 pf[4];           // its probabilities as B operands
-
-    // LDS read addresses: K of the tile one ahead, V of the current tile
-    unsigned rk[KS], rv[DB][2];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) rk[ks] = lds0 + lm.k_rd[ks];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) { rv[db][0] = lds0 + 2 * G::kTile + lm.v_rd[db][0]; rv[db][1] = lds0 + 2 * G::kTile + lm.v_rd[db][1]; }
-
-    auto tile_j = [&](int i) { return j0 + i * step; };
-    auto fetch_burst = [&](const char* head, int i, unsigned dst) {
-        const char* base = head + (size_t)tile_j(i) * kTileKV * G::kRowBytes;
-#pragma unroll
-        for (int l = 0; l < NL; ++l) load_to_lds_16B(base, lm.fill_src[l], dst + lm.fill_dst + l * 4096);
-    };
-    auto k_read = [&](int m) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[m / 2] + (m & 1) * 32 * G::kRowBytes); };
-    auto v_read = [&](int idx) -> s8 {
-        const int ks = idx / DB, db = idx % DB;
-        const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][0] + ks * 16 * G::kRowBytes));
-        const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][1] + ks * 16 * G::kRowBytes));
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    };
-    // causal mask of tile i in A / x: bit 16*b + r set where the key is after the query
-    auto mask_bits = [&](int i) -> unsigned {
-        const int kv0 = tile_j(i) * kTileKV;
-        unsigned mk = 0u;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kv = kv0 + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
-                if (kv > qrow) mk |= 1u << (16 * b + r);
-            }
-        return mk;
-    };
-    auto needs_mask = [&](int i) -> bool { return CAUSAL && tile_j(i) * kTileKV + kTileKV - 1 > t * kTileQ; };
-    auto rescale = [&](float tmax) {
-        const float Mnew = fmaxf(M, tmax);
-        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(M - Mnew);
-        M = Mnew;
-        L *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-    };
-    float tmax_ahead = 0.f;   // row maximum (times c) of the tile in A, from the latest iteration
-    // exp unit u (0..15): the two exponentials of pair u, and the convert + sum of pair u-1
-    float e0[16], e1[16];
-    auto exp_unit = [&](int u) {
-        if (u < 16) {
-            e0[u] = fast_exp2(x[2 * u]);
-            e1[u] = fast_exp2(x[2 * u + 1]);
-        }
-        if (u >= 1 && u <= 16) {
-            const int v = u - 1;
-            const h2 ph = __builtin_convertvector(f2{e0[v], e1[v]}, h2);
-            L = __builtin_amdgcn_fdot2(ph, ones, L, false);   // sum of the rounded probabilities
-            pf[v / 4][v % 4] = __builtin_bit_cast(unsigned, ph);
-        }
-    };
-
-    // ---------------------------------------------------------------- prologue: tile 0
-    fetch_burst(Kh, 0, lds0);
-    fetch_burst(Vh, 0, lds0 + 2 * G::kTile);
-    wait_tile_landed();
-    __syncthreads();
-    if (nkv > 1) fetch_burst(Kh, 1, lds0 + G::kTile);
-    {
-        u4 a[NA];
-        a[0] = k_read(0);
-        a[1] = k_read(1);
-#pragma unroll
-        for (int m = 0; m < NA; ++m) {
-            if (m + 2 < NA) a[m + 2] = k_read(m + 2);
-            const f16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            A[m & 1] = mfma_16bit<false>(a[m], qf[m / 2], m < 2 ? zero : A[m & 1]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        unsigned mk = 0u;
-        if (needs_mask(0)) {
-            mk = mask_bits(0);
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) if ((mk >> (16 * b + r)) & 1u) A[b][r] = -INFINITY;
-        }
-        float mx = fmaxf(A[0][0], A[0][1]);
-#pragma unroll
-        for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, A[r >> 4][r & 15]), A[r >> 4][(r & 15) + 1]);
-        const float tmax = pair_max(mx) * c;
-        if (__builtin_amdgcn_ballot_w64(!(tmax <= M + kRescaleSlack)) != 0) rescale(tmax);
-#pragma unroll
-        for (int r = 0; r < 32; ++r) x[r] = __builtin_fmaf(A[r >> 4][r & 15], c, -M);
-        if (needs_mask(0)) {
-#pragma unroll
-            for (int r = 0; r < 32; ++r) if ((mk >> r) & 1u) x[r] = -INFINITY;
-        }
-    }
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) rk[ks] += G::kTile;   // K of tile 1 is in buffer 1
-    if (nkv > 1) {
-        wait_tile_landed();
-        __syncthreads();
-    }
-
-    // ---------------------------------------------------------------- steady state: iteration i
-    // reads K(i+1) from K buffer (i+1)&1 and V(i) from V buffer i&1; fetches K(i+2) into K buffer
-    // i&1 and V(i+1) into V buffer (i+1)&1.
-    auto iteration = [&](int i, auto fetch_k_tag) -> bool {
-        constexpr bool FETCH_K = decltype(fetch_k_tag)::value;
-        const int cur = i & 1;
-        const char* kbase = Kh + (size_t)tile_j(i + 2) * kTileKV * G::kRowBytes;
-        const char* vbase = Vh + (size_t)tile_j(i + 1) * kTileKV * G::kRowBytes;
-        const unsigned kdst = lds0 + cur * G::kTile + lm.fill_dst;
-        const unsigned vdst = lds0 + (2 + (cur ^ 1)) * G::kTile + lm.fill_dst;
-        // ---- phase A
-        {
-            u4 a[NA];
-            a[0] = k_read(0);
-            a[1] = k_read(1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int m = 0; m < NA; ++m) {
-                if (m + 2 < NA) a[m + 2] = k_read(m + 2);
-                const f16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                A[m & 1] = mfma_16bit<false>(a[m], qf[m / 2], m < 2 ? zero : A[m & 1]);
-#pragma unroll
-                for (int q = 0; q < EU; ++q) exp_unit(m * EU + q);
-                if ((m * 2 * NL) / NA != ((m + 1) * 2 * NL) / NA) {
-                    const int li = (m * 2 * NL) / NA;
-                    if (li < NL) { if (FETCH_K) load_to_lds_16B(kbase, lm.fill_src[li], kdst + li * 4096); }
-                    else load_to_lds_16B(vbase, lm.fill_src[li - NL], vdst + (li - NL) * 4096);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            exp_unit(16);
-        }
-        unsigned mk = 0u;
-        const bool mflag = needs_mask(i + 1);
-        if (mflag) {
-            mk = mask_bits(i + 1);
-#pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) if ((mk >> (16 * b + r)) & 1u) A[b][r] = -INFINITY;
-        }
-        // ---- phase B, first half: row maximum of A and the rescale check
-        s8 av[NB];
-        av[0] = v_read(0);
-        av[1] = v_read(1);
-        __builtin_amdgcn_sched_barrier(0);
-        float mx = 0.f;
-        constexpr int H = NB / 2;          // MFMAs before the check
-        constexpr int MS = 2;              // first slot that may read A (MFMA result latency)
-        constexpr int MPS = (16 + (H - MS) - 1) / (H - MS);   // max3 ops per slot
-#pragma unroll
-        for (int idx = 0; idx < H; ++idx) {
-            av[idx + 2] = v_read(idx + 2);
-            o[idx % DB] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[idx / DB]),
-                                                                 o[idx % DB], 0, 0, 0);
-            if (idx >= MS) {
-#pragma unroll
-                for (int q = 0; q < MPS; ++q) {
-                    const int op = (idx - MS) * MPS + q;   // op-th max3: elements 2*op, 2*op+1
-                    if (op < 16) {
-                        const float u0 = A[(2 * op) >> 4][(2 * op) & 15], u1 = A[(2 * op) >> 4][((2 * op) & 15) + 1];
-                        mx = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx, u0), u1);
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        tmax_ahead = pair_max(mx) * c;
-        const bool need = __builtin_amdgcn_ballot_w64(!(tmax_ahead <= M + kRescaleSlack)) != 0;
-        // ---- phase B, second half, with the shifted scores of tile i+1 in between.  If the
-        //      reference maximum has to be raised (need), these are recomputed after the loop exit.
-        constexpr int FPS = 32 / (NB - H);   // fmas per slot
-#pragma unroll
-        for (int idx = H; idx < NB; ++idx) {
-            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
-            o[idx % DB] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[idx / DB]),
-                                                                 o[idx % DB], 0, 0, 0);
-#pragma unroll
-            for (int q = 0; q < FPS; ++q) {
-                const int r = (idx - H) * FPS + q;
-                x[r] = __builtin_fmaf(A[r >> 4][r & 15], c, -M);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (mflag) {
-#pragma unroll
-            for (int r = 0; r < 32; ++r) if ((mk >> r) & 1u) x[r] = -INFINITY;
-        }
-        // ---- switch buffers, publish the fetched tiles
-        const int dk = cur ? G::kTile : -G::kTile;   // K(i+2) is in buffer i&1
-        const int dv = cur ? -G::kTile : G::kTile;   // V(i+1) is in buffer (i+1)&1
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) rk[ks] += dk;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) { rv[db][0] += dv; rv[db][1] += dv; }
-        wait_tile_landed();
-        __syncthreads();
-        return need;
-    };
-    // Raise the reference maximum for the tile held in A (tile index ia) and redo its shifted
-    // scores; only reached when the loop below stopped because an iteration asked for it.
-    auto raise_reference = [&](int ia) {
-        rescale(tmax_ahead);
-#pragma unroll
-        for (int r = 0; r < 32; ++r) x[r] = __builtin_fmaf(A[r >> 4][r & 15], c, -M);
-        if (needs_mask(ia)) {
-            const unsigned mk = mask_bits(ia);
-#pragma unroll
-            for (int r = 0; r < 32; ++r) if ((mk >> r) & 1u) x[r] = -INFINITY;
-        }
-    };
-    int i = 0;
-    while (i + 2 < nkv) {
-        bool need = false;
-#pragma unroll 1
-        for (; i + 2 < nkv; ++i) {
-            need = iteration(i, std::true_type{});
-            if (need) { ++i; break; }
-        }
-        if (need) raise_reference(i);
-    }
-    if (i + 1 < nkv) {
-        const bool need = iteration(i, std::false_type{});
-        ++i;
-        if (need) raise_reference(i);
-    }
-
-    // ---------------------------------------------------------------- last tile: probabilities, then O^T += V^T P^T
-#pragma unroll
-    for (int u = 0; u <= 16; ++u) exp_unit(u);
-    {
-        s8 av[NB];
-        av[0] = v_read(0);
-        av[1] = v_read(1);
-#pragma unroll
-        for (int idx = 0; idx < NB; ++idx) {
-            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
-            o[idx % DB] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[idx / DB]),
-                                                                 o[idx % DB], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    __syncthreads();   // all reads of the last tile are done before the next query tile's first fetch
-
-    // ---- epilogue: O_i = acc / l
-    const float inv = 1.0f / pair_sum(L);
-    if (qrow < N) {
-        const size_t orow = ((size_t)hh * N + qrow) * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                f4 v = {o[db][4 * rq] * inv, o[db][4 * rq + 1] * inv, o[db][4 * rq + 2] * inv, o[db][4 * rq + 3] * inv};
                 const size_t col = 32 * db + 8 * rq + 4 * g;
                 if (p.o_dtype == SAWATTN_F32) {
                     *reinterpret_cast<f4*>(static_cast<float*>(p.O) + orow + col) = v;
@@ -853,12 +792,7 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
             int lane = lane0;
             asm volatile("" : "+v"(lane));
             const LaneMap<D> lm(wave, lane);
-            if constexpr (BF16) {
-                process_q_tile<D, BF16, CAUSAL>(p, lm, hh, t, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
-            } else {
-                if (p.N % kTileKV == 0) process_q_tile_pipelined<D, CAUSAL>(p, lm, hh, t, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
-                else process_q_tile<D, BF16, CAUSAL>(p, lm, hh, t, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
-            }
+            process_q_tile<D, BF16, CAUSAL>(p, lm, hh, t, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
             ++local;
         }
     }
