@@ -2,8 +2,7 @@
 //
 // One workgroup = 4 wavefronts = one 128-row query tile (paper Sec. 2.2, Alg. 1); wavefront w owns
 // query rows 32w..32w+31 of the tile and keeps them in registers for the whole inner loop.  K and V
-// are streamed in 64-row tiles through two LDS buffers each (global -> registers -> LDS, the next
-// tile in flight while the current one is used).
+// are streamed in 64-row tiles through two LDS buffers each, filled by direct global->LDS loads.
 //
 // Both contractions run on v_mfma_f32_32x32x16 in the transposed form
 //     S^T (kv x q) = K_j   (kv x d) . Q_i^T (d x q)
@@ -19,6 +18,10 @@
 // Softmax statistics live per lane: lanes l and l+32 share a query row and hold disjoint key
 // subsets, so the running maximum is merged across the pair every tile while the running sum stays
 // a per-lane partial (it is linear) and is merged once in the epilogue.
+//
+// A query tile's scan is a software-pipelined run of full, unmasked K/V tiles (pipelined_range)
+// plus, at one end, a short run of masked tiles (general_range).  The workgroups of one XCD walk
+// the same head together and re-align between heads (domain_sync).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
