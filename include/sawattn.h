@@ -43,7 +43,7 @@ enum {
  *            (SAWATTN_F16 or SAWATTN_BF16), 16-byte aligned.  Query and key sequences both have
  *            length N; each (batch, head) pair is an independent attention problem.
  *   O        device, written.  Contiguous [B, H, N, d], element type `o_dtype` (F16, BF16 or F32),
- *            16-byte aligned.  Every element is overwritten.
+ *            16-byte aligned.  Every element is overwritten.  Must not overlap Q, K or V.
  *   B, H, N  >= 1.   d must be 64 or 128.   B*H*N*d must be below 2^40 and B*H*ceil(N/128) below 2^31.
  *   scale    any finite float (1/sqrt(d) in the paper); the scores are multiplied by it.
  *   causal   0: every key is visible;  non-zero: key j is visible to query i iff j <= i.
@@ -56,7 +56,13 @@ enum {
  * running maximum, the running sum and the output accumulator are fp32; the probabilities are
  * rounded to binary16 before the second contraction (for bf16 inputs V is converted to binary16 on
  * the way into LDS, which is exact for |v| in [2^-14, 65504] -- larger bf16 values of V are not
- * supported).  The caller owns every buffer; the library keeps no state besides the error text.
+ * supported).  The caller owns every buffer.  Besides the per-thread error text the library holds
+ * one piece of device state: eight 32-bit arrival counters (one per XCD) with which the workgroups
+ * of an XCD wait for each other, for a bounded time, before they move on to the next head, so that
+ * they keep streaming the same K/V through their shared L2.  A launch that has more than one head
+ * per XCD clears them first (a one-block kernel on the same stream).  The counters steer timing
+ * only: launches that overlap on one device share them, which can cost L2 hits, never correctness,
+ * and no wait is unbounded.
  *
  * Errors: INVALID_ARG / UNSUPPORTED as listed above (nothing is launched); RUNTIME if the launch
  * fails.  Safe to call from several host threads.

@@ -28,6 +28,7 @@
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <type_traits>
 #include <utility>
 
@@ -963,6 +964,15 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         return fail(SAWATTN_ERR_INVALID_ARG, "o_dtype must be SAWATTN_F16, SAWATTN_BF16 or SAWATTN_F32");
     if ((trace == nullptr) != (trace_count == nullptr))
         return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be given together");
+    {   // A workgroup writes its O rows while others still read Q, K, V: O may not share memory with them.
+        const unsigned long long elems = (unsigned long long)B * H * N * d;
+        const unsigned long long in_bytes = elems * 2u, out_bytes = elems * (o_dtype == SAWATTN_F32 ? 4u : 2u);
+        const uintptr_t o0 = (uintptr_t)O, o1 = o0 + out_bytes;
+        for (const void* in : {Q, K, V}) {
+            const uintptr_t i0 = (uintptr_t)in, i1 = i0 + in_bytes;
+            if (o0 < i1 && i0 < o1) return fail(SAWATTN_ERR_INVALID_ARG, "O must not overlap Q, K or V");
+        }
+    }
 
     Params p;
     p.Q = Q; p.K = K; p.V = V; p.O = O;

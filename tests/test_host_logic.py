@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol(sa):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", header)
     assert set(names) >= {"attn_fwd", "attn_fwd_trace", "attn_fwd_launch_info", "attn_fwd_plan",
-                          "sawattn_last_error", "sawattn_version"}
+                          "sawattn_mfma_probe", "sawattn_last_error", "sawattn_version"}
     L = sa.lib()
     for n in names:
         assert hasattr(L, n), f"{n} is declared in sawattn.h but not exported"
@@ -37,7 +37,7 @@ def test_argument_validation_without_a_gpu(sa):
     """Every case below is rejected before anything is launched, so fake pointers are safe."""
     L = sa.lib()
     ok_ptr = 0x1000
-    base = dict(Q=ok_ptr, K=ok_ptr, V=ok_ptr, O=ok_ptr, B=1, H=1, N=128, d=64, scale=0.125, causal=0,
+    base = dict(Q=ok_ptr, K=ok_ptr, V=ok_ptr, O=0x100000, B=1, H=1, N=128, d=64, scale=0.125, causal=0,
                 scan=1, idt=0, odt=0)
 
     def call(**kw):
@@ -58,6 +58,9 @@ def test_argument_validation_without_a_gpu(sa):
     assert call(scan=2) == binding.ERR_INVALID_ARG
     assert call(idt=2) == binding.ERR_INVALID_ARG                 # fp32 inputs are not accepted
     assert call(odt=3) == binding.ERR_INVALID_ARG
+    assert call(O=ok_ptr + 128 * 64 * 2 - 16) == binding.ERR_INVALID_ARG   # O starts inside Q
+    assert "overlap" in sa.sawattn_last_error()
+    assert call(Q=0x100000, K=0x200000, V=0x300000, O=0x300000 - 128 * 64 * 4 + 16, odt=2) == binding.ERR_INVALID_ARG
     assert call(B=1 << 20, H=1 << 10, N=1 << 20) == binding.ERR_INVALID_ARG   # size overflow
     with pytest.raises(binding.SawattnError):
         sa.attn_fwd_launch_info(1, 1, 128, 80)
