@@ -71,12 +71,63 @@ int attn_fwd(const void* Q, const void* K, const void* V, void* O,
              int B, int H, int N, int d, float scale, int causal, int scan_order,
              int in_dtype, int o_dtype, void* hip_stream);
 
+/*
+ * Launch variants (paper Sec. 2.2 Alg. 2 and Alg. 3, Sec. 3.4, Sec. 4.3), selectable so that they can be
+ * measured against the default.  All compute the same O; only which workgroup takes which query tile,
+ * when, and in which direction it walks K/V differs.
+ */
+enum {
+    SAWATTN_LAUNCH_PERSISTENT = 0, /* Alg. 2: a fixed set of workgroups loops over the query tiles */
+    SAWATTN_LAUNCH_GRID = 1        /* Alg. 3: one workgroup per `tiles_per_workgroup` consecutive query
+                                      tiles, handed to the hardware dispatcher */
+};
+enum {
+    SAWATTN_DECODE_DOMAIN = 0,     /* work is dealt out per XCD (one L2 each): the workgroups of an XCD
+                                      share one head's K/V at a time; causal heads start with their
+                                      longest tiles */
+    SAWATTN_DECODE_LINEAR = 1      /* as printed: one linear index over (batch, head, tile), tile fastest;
+                                      persistent workgroup k takes k, k+G, k+2G, ... */
+};
+typedef struct sawattn_variant {
+    int launch;              /* SAWATTN_LAUNCH_* */
+    int decode;              /* SAWATTN_DECODE_* */
+    int slots_per_domain;    /* persistent launch: at most this many workgroups per XCD (1..64), so
+                                G = 8 * slots (Sec. 3.4's resident-CTA sweep); 0 = default (64).
+                                Ignored by the grid launch. */
+    int tiles_per_workgroup; /* grid launch: 1, or 2 = forward over the first tile and, with the sawtooth
+                                order, backward over the second (Sec. 4.3's step-2 alternation);
+                                0 = default (2).  Ignored by the persistent launch. */
+} sawattn_variant;
+/*
+ * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round
+ * over the current head (the default); persistent + linear decode: parity of the workgroup's own
+ * iteration count (Alg. 4 as printed); grid launch: parity of the tile's position in its workgroup.
+ * A NULL variant pointer selects { PERSISTENT, DOMAIN, 0, 0 }, which is what attn_fwd runs.
+ */
+
+/*
+ * attn_fwd_variant -- attn_fwd under a launch variant, optionally recording the schedule: every
+ * workgroup notes which query tile it took at each of its local iterations and in which direction it
+ * walked the K/V tiles (paper Sec. 2.2 Alg. 2/3 work decode, Sec. 4 Alg. 4 scan direction).
+ *
+ *   variant      host, read during the call only; NULL = default.
+ *   trace        device, written, or NULL: int32 [grid][max_local_tiles][4] = (b*H + h, query tile
+ *                index, first K/V tile visited, last K/V tile visited); grid and max_local_tiles from
+ *                attn_fwd_launch_info for the same variant.  Unused records are left untouched.
+ *   trace_count  device, written, or NULL (both or neither): int32 [grid], records each workgroup wrote.
+ * All other arguments, errors and stream behaviour as attn_fwd; INVALID_ARG for a bad variant field.
+ */
+int attn_fwd_variant(const void* Q, const void* K, const void* V, void* O,
+                     int B, int H, int N, int d, float scale, int causal, int scan_order,
+                     int in_dtype, int o_dtype, void* hip_stream,
+                     const sawattn_variant* variant, int32_t* trace, int32_t* trace_count);
+
 /* Launch geometry chosen for a problem; filled by attn_fwd_launch_info (host memory). */
 typedef struct sawattn_launch_info {
     int tile_q;            /* query rows per workgroup tile */
     int tile_kv;           /* key/value rows per streamed tile */
     int block_threads;     /* threads per workgroup (64-wide wavefronts) */
-    int grid;              /* persistent workgroups launched, a multiple of `domains` */
+    int grid;              /* workgroups launched, a multiple of `domains` */
     int lds_bytes;         /* dynamic LDS per workgroup */
     int domains;           /* cache domains (XCDs, one L2 each) the schedule is built for */
     int slots;             /* workgroups per domain = grid / domains */
@@ -86,37 +137,24 @@ typedef struct sawattn_launch_info {
 } sawattn_launch_info;
 
 /*
- * attn_fwd_launch_info -- report the geometry attn_fwd would use (paper Sec. 2.2, Alg. 2: grid size
- * and work decode).  `out` is host memory.  Validates B, H, N, d like attn_fwd.  Launches nothing.
+ * attn_fwd_launch_info -- report the geometry attn_fwd (variant NULL) or attn_fwd_variant would use
+ * (paper Sec. 2.2, Alg. 2 / Alg. 3: grid size and work decode).  `variant` and `out` are host memory.
+ * Validates B, H, N, d and the variant like attn_fwd_variant.  Launches nothing.
  */
-int attn_fwd_launch_info(int B, int H, int N, int d, int causal, sawattn_launch_info* out);
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_variant* variant,
+                         sawattn_launch_info* out);
 
 /*
- * attn_fwd_trace -- attn_fwd, and in addition every workgroup records which query tile it took at
- * each of its local iterations and in which direction it walked the K/V tiles (paper Sec. 2.2
- * Alg. 2 work decode, Sec. 4 Alg. 4 scan direction), so that the schedule can be checked.
+ * attn_fwd_plan -- the schedule attn_fwd_variant would run, computed on the host from the same work
+ * decode the kernel uses (paper Sec. 2.2 Alg. 2/3, Sec. 4 Alg. 4).  Launches nothing and needs no GPU.
  *
- *   trace        device, written: int32 [grid][max_local_tiles][4] = (b*H + h, query tile index,
- *                first K/V tile visited, last K/V tile visited); grid and max_local_tiles from
- *                attn_fwd_launch_info.  Unused records are left untouched.
- *   trace_count  device, written: int32 [grid], the number of records each workgroup wrote.
- * All other arguments, errors and stream behaviour as attn_fwd.
- */
-int attn_fwd_trace(const void* Q, const void* K, const void* V, void* O,
-                   int B, int H, int N, int d, float scale, int causal, int scan_order,
-                   int in_dtype, int o_dtype, void* hip_stream,
-                   int32_t* trace, int32_t* trace_count);
-
-/*
- * attn_fwd_plan -- the schedule attn_fwd would run, computed on the host from the same work decode
- * the kernel uses (paper Sec. 2.2 Alg. 2, Sec. 4 Alg. 4).  Launches nothing and needs no GPU.
- *
+ *   variant      host or NULL, as for attn_fwd_variant.
  *   trace        host, written: int32 [grid][max_local_tiles][4], same record layout as
- *                attn_fwd_trace; unused records are left untouched.
+ *                attn_fwd_variant; unused records are left untouched.
  *   trace_count  host, written: int32 [grid].
- * B, H, N, d, causal, scan_order are validated like attn_fwd.
+ * B, H, N, d, causal, scan_order and the variant are validated like attn_fwd_variant.
  */
-int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order,
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const sawattn_variant* variant,
                   int32_t* trace, int32_t* trace_count);
 
 /*

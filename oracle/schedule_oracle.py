@@ -17,6 +17,16 @@ domain.
     restarting with every chunk (a new chunk brings new K/V, so there is nothing to re-use by
     walking backward into it); N_KV is the number of K/V tiles visible to the query tile.
 
+Variants kept for comparison (same records, other hand-out):
+  * `slots_per_domain`: fewer resident workgroups per domain (Sec. 3.4's sweep over active CTAs).
+  * decode "linear": the printed Alg. 2 -- one list of all (head, tile) pairs, tile fastest;
+    persistent workgroup k takes entries k, k+G, k+2G, ... and walks backward on its odd local
+    iterations (Alg. 4 as printed).
+  * launch "grid" (Alg. 3): one workgroup per `tiles_per_workgroup` consecutive entries of the
+    list (linear decode) or of a chunk's tile list (domain decode, workgroups of a domain
+    numbered chunk after chunk); with two tiles per workgroup the second is walked backward
+    under the sawtooth order (Sec. 4.3, the variant that advances the loop by two).
+
 Nothing here is shared with the GPU library.
 """
 from __future__ import annotations
@@ -30,44 +40,87 @@ def ceil_div(a: int, b: int) -> int:
     return -(-a // b)
 
 
-def launch_geometry(B: int, H: int, N: int):
+def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",
+                    slots_per_domain: int = MAX_SLOTS, tiles_per_workgroup: int = 2):
     heads = B * H
     q_tiles = ceil_div(N, T_Q)
+    total = heads * q_tiles
+    if decode == "linear":
+        if launch == "persistent":
+            slots = min(ceil_div(total, DOMAINS), slots_per_domain)
+            local = ceil_div(total, DOMAINS * slots)
+        else:
+            slots = ceil_div(ceil_div(total, tiles_per_workgroup), DOMAINS)
+            local = tiles_per_workgroup
+        return {"grid": DOMAINS * slots, "slots": slots, "parts": 1, "q_tiles": q_tiles, "max_local": local}
     parts = DOMAINS // gcd(heads, DOMAINS)
     largest_part = ceil_div(q_tiles, parts)
-    slots = min(largest_part, MAX_SLOTS)
-    rounds = ceil_div(largest_part, slots)
+    chunks_per_domain = heads * parts // DOMAINS
+    if launch == "persistent":
+        slots = min(largest_part, slots_per_domain)
+        rounds = ceil_div(largest_part, slots)
+        return {"grid": DOMAINS * slots, "slots": slots, "parts": parts, "q_tiles": q_tiles,
+                "rounds_per_chunk": rounds, "chunks_per_domain": chunks_per_domain,
+                "max_local": chunks_per_domain * rounds}
+    units = ceil_div(largest_part, tiles_per_workgroup)
+    slots = chunks_per_domain * units
     return {"grid": DOMAINS * slots, "slots": slots, "parts": parts, "q_tiles": q_tiles,
-            "rounds_per_chunk": rounds, "chunks_per_domain": heads * parts // DOMAINS}
+            "units_per_chunk": units, "chunks_per_domain": chunks_per_domain, "max_local": tiles_per_workgroup}
 
 
-def schedule(B: int, H: int, N: int, causal: bool, scan_order: str):
+def visible_kv(t: int, N: int, causal: bool) -> int:
+    """Number of K/V tiles query tile t has to visit."""
+    if not causal:
+        return ceil_div(N, T_KV)
+    last_row = min((t + 1) * T_Q, N)          # rows of the tile are t*T_Q .. last_row-1
+    return ceil_div(last_row, T_KV)
+
+
+def record(head: int, t: int, N: int, causal: bool, backward: bool):
+    n_kv = visible_kv(t, N, causal)
+    return (head, t, n_kv - 1, 0) if backward else (head, t, 0, n_kv - 1)
+
+
+def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str = "persistent",
+             decode: str = "domain", slots_per_domain: int = MAX_SLOTS, tiles_per_workgroup: int = 2):
     """Return {workgroup: [(head, query tile, first K/V tile, last K/V tile), ...]} in the order
     each workgroup processes its tiles."""
-    geo = launch_geometry(B, H, N)
-    heads, parts, slots = B * H, geo["parts"], geo["slots"]
-    kv_tiles = ceil_div(N, T_KV)
+    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup)
+    heads, parts, slots, grid = B * H, geo["parts"], geo["slots"], geo["grid"]
+    saw = scan_order == "sawtooth"
     out = {}
-    for wg in range(geo["grid"]):
-        domain, slot = wg % DOMAINS, wg // DOMAINS
+    if decode == "linear":
+        work = [(head, t) for head in range(heads) for t in range(geo["q_tiles"])]
+        for wg in range(grid):
+            mine = work[wg::grid] if launch == "persistent" else \
+                work[wg * tiles_per_workgroup:(wg + 1) * tiles_per_workgroup]
+            out[wg] = [record(head, t, N, causal, saw and i % 2 == 1) for i, (head, t) in enumerate(mine)]
+        return out
+    for domain in range(DOMAINS):
         my_chunks = [c for c in range(heads * parts) if c % DOMAINS == domain]
-        recs = []
+        chunk_tiles = []
         for c in my_chunks:
             head, part = divmod(c, parts)
             tiles = list(range(part, geo["q_tiles"], parts))
             if causal:
                 tiles.reverse()                       # longest tile first
-            for r in range(geo["rounds_per_chunk"]):
-                hand_out = list(range(slots)) if r % 2 == 0 else list(range(slots - 1, -1, -1))
-                pos = r * slots + hand_out.index(slot)
-                if pos < len(tiles):
-                    t = tiles[pos]
-                    if causal:
-                        last_row = min((t + 1) * T_Q, N)   # rows of the tile are t*T_Q .. last_row-1
-                        n_kv = ceil_div(last_row, T_KV)
-                    else:
-                        n_kv = kv_tiles
-                    backward = scan_order == "sawtooth" and r % 2 == 1
-                    recs.append((head, t, n_kv - 1, 0) if backward else (head, t, 0, n_kv - 1))
-        out[wg] = recs
+            chunk_tiles.append((head, tiles))
+        if launch == "grid":
+            m = 0                                     # workgroups of the domain, chunk after chunk
+            for head, tiles in chunk_tiles:
+                for unit in range(geo["units_per_chunk"]):
+                    mine = tiles[unit * tiles_per_workgroup:(unit + 1) * tiles_per_workgroup]
+                    out[m * DOMAINS + domain] = [record(head, t, N, causal, saw and i % 2 == 1)
+                                                 for i, t in enumerate(mine)]
+                    m += 1
+            continue
+        for slot in range(slots):
+            recs = []
+            for head, tiles in chunk_tiles:
+                for r in range(geo["rounds_per_chunk"]):
+                    hand_out = list(range(slots)) if r % 2 == 0 else list(range(slots - 1, -1, -1))
+                    pos = r * slots + hand_out.index(slot)
+                    if pos < len(tiles):
+                        recs.append(record(head, tiles[pos], N, causal, saw and r % 2 == 1))
+            out[slot * DOMAINS + domain] = recs
     return out

@@ -16,6 +16,9 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_RUNTIME = 0, 1, 2, 3
 SCAN_CYCLIC, SCAN_SAWTOOTH = 0, 1
 F16, BF16, F32 = 0, 1, 2
 
+LAUNCH_PERSISTENT, LAUNCH_GRID = 0, 1
+DECODE_DOMAIN, DECODE_LINEAR = 0, 1
+
 _DTYPE_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
 _SCAN_CODE = {"cyclic": SCAN_CYCLIC, "sawtooth": SCAN_SAWTOOTH, SCAN_CYCLIC: SCAN_CYCLIC,
               SCAN_SAWTOOTH: SCAN_SAWTOOTH}
@@ -28,6 +31,25 @@ class LaunchInfo(ctypes.Structure):
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Variant(ctypes.Structure):
+    """sawattn_variant: which launch / work decode to run (None everywhere = the default)."""
+    _fields_ = [("launch", ctypes.c_int), ("decode", ctypes.c_int), ("slots_per_domain", ctypes.c_int),
+                ("tiles_per_workgroup", ctypes.c_int)]
+
+
+_LAUNCH_CODE = {"persistent": LAUNCH_PERSISTENT, "grid": LAUNCH_GRID}
+_DECODE_CODE = {"domain": DECODE_DOMAIN, "linear": DECODE_LINEAR}
+
+
+def variant(launch="persistent", decode="domain", slots_per_domain=0, tiles_per_workgroup=0) -> Variant:
+    return Variant(_LAUNCH_CODE.get(launch, launch), _DECODE_CODE.get(decode, decode),
+                   int(slots_per_domain), int(tiles_per_workgroup))
+
+
+def _vptr(v):
+    return ctypes.byref(v) if v is not None else None
 
 
 class SawattnError(RuntimeError):
@@ -51,12 +73,13 @@ def lib() -> ctypes.CDLL:
         vp, ci = ctypes.c_void_p, ctypes.c_int
         L.attn_fwd.restype = ci
         L.attn_fwd.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, ci, ci, ci, vp]
-        L.attn_fwd_trace.restype = ci
-        L.attn_fwd_trace.argtypes = L.attn_fwd.argtypes + [vp, vp]
+        pv = ctypes.POINTER(Variant)
+        L.attn_fwd_variant.restype = ci
+        L.attn_fwd_variant.argtypes = L.attn_fwd.argtypes + [pv, vp, vp]
         L.attn_fwd_launch_info.restype = ci
-        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(LaunchInfo)]
+        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, pv, ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_plan.restype = ci
-        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ci, ci, vp, vp]
+        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ci, ci, pv, vp, vp]
         L.sawattn_mfma_probe.restype = ci
         L.sawattn_mfma_probe.argtypes = [vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
         L.sawattn_last_error.restype = ctypes.c_char_p
@@ -80,18 +103,19 @@ def _check(rc: int):
         raise SawattnError(rc, sawattn_last_error())
 
 
-def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False) -> dict:
+def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False, variant: Variant = None) -> dict:
     info = LaunchInfo()
-    _check(lib().attn_fwd_launch_info(B, H, N, d, int(bool(causal)), ctypes.byref(info)))
+    _check(lib().attn_fwd_launch_info(B, H, N, d, int(bool(causal)), _vptr(variant), ctypes.byref(info)))
     return info.as_dict()
 
 
-def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_order="sawtooth"):
+def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_order="sawtooth",
+                  variant: Variant = None):
     """Host-side schedule: returns (trace[grid, max_local, 4], count[grid]) as CPU int32 tensors."""
-    info = attn_fwd_launch_info(B, H, N, d, causal)
+    info = attn_fwd_launch_info(B, H, N, d, causal, variant)
     trace = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32)
     count = torch.zeros((info["grid"],), dtype=torch.int32)
-    _check(lib().attn_fwd_plan(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order],
+    _check(lib().attn_fwd_plan(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order], _vptr(variant),
                                trace.data_ptr(), count.data_ptr()))
     return trace, count
 
@@ -132,18 +156,21 @@ def attn_fwd(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order=
     return O
 
 
-def attn_fwd_trace(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order="sawtooth",
-                   o_dtype=None, stream=None):
-    """attn_fwd plus the schedule record; returns (O, trace[grid, max_local, 4], count[grid])."""
+def attn_fwd_variant(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order="sawtooth",
+                     o_dtype=None, stream=None, variant: Variant = None, trace: bool = False):
+    """attn_fwd under a launch variant.  Returns O, or with trace=True (O, trace[grid, max_local, 4],
+    count[grid]): the schedule the workgroups recorded."""
     O = _marshal(Q, K, V, O, o_dtype)
     B, H, N, d = Q.shape
-    info = attn_fwd_launch_info(B, H, N, d, causal)
-    trace = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32,
-                       device=Q.device)
-    count = torch.zeros((info["grid"],), dtype=torch.int32, device=Q.device)
+    tr = cnt = None
+    if trace:
+        info = attn_fwd_launch_info(B, H, N, d, causal, variant)
+        tr = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32,
+                        device=Q.device)
+        cnt = torch.zeros((info["grid"],), dtype=torch.int32, device=Q.device)
     st = stream if stream is not None else torch.cuda.current_stream(Q.device)
-    _check(lib().attn_fwd_trace(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
-                                float(scale), int(bool(causal)), _SCAN_CODE[scan_order],
-                                _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream,
-                                trace.data_ptr(), count.data_ptr()))
-    return O, trace, count
+    _check(lib().attn_fwd_variant(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                  float(scale), int(bool(causal)), _SCAN_CODE[scan_order],
+                                  _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream, _vptr(variant),
+                                  tr.data_ptr() if trace else None, cnt.data_ptr() if trace else None))
+    return (O, tr, cnt) if trace else O

@@ -807,35 +807,29 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
     const Schedule& s = p.sched;
     const int lane0 = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int domain = blockIdx.x % kDomains;
-    const int slot = blockIdx.x / kDomains;
     int local = 0;           // query tiles this workgroup has processed
-    for (int cs = 0; cs < s.chunks_per_domain; ++cs) {
-        for (int r = 0; r < s.rounds_per_chunk; ++r) {
-            int hh;
-            const int t = decode_tile(s, domain, slot, cs, r, CAUSAL, &hh);
-            if (t >= 0) {
-                const int nkv = visible_kv_tiles(s, t, p.N, CAUSAL);
-                const bool backward = p.sawtooth && (r & 1);
-                const int j0 = backward ? nkv - 1 : 0;
-                const int step = backward ? -1 : 1;
-                if (p.trace && threadIdx.x == 0) {
-                    int32_t* rec = p.trace + ((size_t)blockIdx.x * p.max_local + local) * 4;
-                    rec[0] = hh; rec[1] = t; rec[2] = j0; rec[3] = j0 + (nkv - 1) * step;
-                }
-                // The per-lane address tables are rebuilt for every query tile from a lane index the
-                // compiler cannot see through, so that they are not kept in registers across the loops.
-                int lane = lane0;
-                asm volatile("" : "+v"(lane));
-                const LaneMap<D> lm(wave, lane);
-                process_q_tile<D, BF16, CAUSAL>(p, lm, hh, t, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
-                ++local;
+    for (int it = 0; it < s.local_iters; ++it) {
+        const Work w = decode_work(s, (int)blockIdx.x, it, CAUSAL, p.sawtooth != 0);
+        if (w.tile >= 0) {
+            const int nkv = visible_kv_tiles(s, w.tile, p.N, CAUSAL);
+            const int j0 = w.backward ? nkv - 1 : 0;
+            const int step = w.backward ? -1 : 1;
+            if (p.trace && threadIdx.x == 0) {
+                int32_t* rec = p.trace + ((size_t)blockIdx.x * p.max_local + local) * 4;
+                rec[0] = w.head; rec[1] = w.tile; rec[2] = j0; rec[3] = j0 + (nkv - 1) * step;
             }
+            // The per-lane address tables are rebuilt for every query tile from a lane index the
+            // compiler cannot see through, so that they are not kept in registers across the loops.
+            int lane = lane0;
+            asm volatile("" : "+v"(lane));
+            const LaneMap<D> lm(wave, lane);
+            process_q_tile<D, BF16, CAUSAL>(p, lm, w.head, w.tile, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
+            ++local;
         }
-        // Every workgroup of the domain comes here once per chunk, also those that sat rounds out.
+        // Every workgroup of the domain comes here once per head, also those that sat rounds out.
         // (Re-aligning after every round as well brings workload 4's L2 misses down to the
         // one-miss-per-line-per-round ideal, but costs 4 % in time; between heads it is free.)
-        if (cs + 1 < s.chunks_per_domain) domain_sync(domain, s.slots);
+        if (w.sync_after) domain_sync((int)blockIdx.x % kDomains, s.slots);
     }
     if (p.trace_count && threadIdx.x == 0) p.trace_count[blockIdx.x] = local;
 }
@@ -916,13 +910,13 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
     out->tile_q = kTileQ;
     out->tile_kv = kTileKV;
     out->block_threads = kThreads;
-    out->grid = kDomains * s.slots;
+    out->grid = s.grid;
     out->lds_bytes = d == 128 ? Geo<128>::kLdsBytes : Geo<64>::kLdsBytes;
     out->domains = kDomains;
     out->slots = s.slots;
     out->parts_per_head = s.parts;
     out->q_tiles_per_head = s.q_tiles;
-    out->max_local_tiles = s.chunks_per_domain * s.rounds_per_chunk;
+    out->max_local_tiles = s.local_iters;
 }
 
 template <int D, bool BF16, bool CAUSAL>
@@ -937,7 +931,8 @@ int launch(const Params& p, int grid, hipStream_t stream) {
         }
         configured = true;
     }
-    if (p.sched.chunks_per_domain > 1) hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream);
+    if (p.sched.launch == kLaunchPersistent && p.sched.decode == kDecodeDomain && p.sched.chunks_per_domain > 1)
+        hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), Geo<D>::kLdsBytes, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -948,9 +943,34 @@ int launch(const Params& p, int grid, hipStream_t stream) {
     return SAWATTN_OK;
 }
 
+// Validates a variant description (NULL = the default schedule) and builds its schedule.
+int schedule_for(int B, int H, int N, const sawattn_variant* v, Schedule* out) {
+    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = kMaxSlots, tiles_per_wg = 2;
+    if (v) {
+        if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
+        if (v->decode != SAWATTN_DECODE_DOMAIN && v->decode != SAWATTN_DECODE_LINEAR)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.decode must be SAWATTN_DECODE_DOMAIN or SAWATTN_DECODE_LINEAR");
+        if (v->slots_per_domain < 0 || v->slots_per_domain > kMaxSlots)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.slots_per_domain must be 0 (default) or 1..64");
+        if (v->tiles_per_workgroup < 0 || v->tiles_per_workgroup > 2)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.tiles_per_workgroup must be 0 (default), 1 or 2");
+        launch = v->launch == SAWATTN_LAUNCH_GRID ? kLaunchGrid : kLaunchPersistent;
+        decode = v->decode == SAWATTN_DECODE_LINEAR ? kDecodeLinear : kDecodeDomain;
+        if (v->slots_per_domain) max_slots = v->slots_per_domain;
+        if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
+    }
+    *out = make_schedule(B * H, N, launch, decode, max_slots, tiles_per_wg);
+    return SAWATTN_OK;
+}
+
 int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale, int causal,
-        int scan_order, int in_dtype, int o_dtype, void* hip_stream, int32_t* trace, int32_t* trace_count) {
+        int scan_order, int in_dtype, int o_dtype, void* hip_stream, const sawattn_variant* variant, int32_t* trace,
+        int32_t* trace_count) {
     int rc = check_shape(B, H, N, d);
+    if (rc != SAWATTN_OK) return rc;
+    Schedule sched;
+    rc = schedule_for(B, H, N, variant, &sched);
     if (rc != SAWATTN_OK) return rc;
     if (!Q || !K || !V || !O) return fail(SAWATTN_ERR_INVALID_ARG, "Q, K, V and O must be non-null");
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u)
@@ -982,9 +1002,9 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.sawtooth = scan_order == SAWATTN_SCAN_SAWTOOTH;
     p.negate_q = scale < 0.f;
     p.c = (float)(std::fabs((double)scale) * 1.4426950408889634074);
-    p.sched = make_schedule(B * H, N);
-    p.max_local = p.sched.chunks_per_domain * p.sched.rounds_per_chunk;
-    const int grid = kDomains * p.sched.slots;
+    p.sched = sched;
+    p.max_local = sched.local_iters;
+    const int grid = sched.grid;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool bf = in_dtype == SAWATTN_BF16, ca = causal != 0;
     if (d == 128) {
@@ -1001,49 +1021,51 @@ extern "C" {
 
 int attn_fwd(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale, int causal,
              int scan_order, int in_dtype, int o_dtype, void* hip_stream) {
-    return sawattn::run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, nullptr, nullptr);
+    return sawattn::run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, nullptr, nullptr,
+                        nullptr);
 }
 
-int attn_fwd_trace(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
-                   int causal, int scan_order, int in_dtype, int o_dtype, void* hip_stream, int32_t* trace,
-                   int32_t* trace_count) {
-    if (!trace || !trace_count) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be non-null");
-    return sawattn::run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, trace, trace_count);
+int attn_fwd_variant(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                     int causal, int scan_order, int in_dtype, int o_dtype, void* hip_stream,
+                     const sawattn_variant* variant, int32_t* trace, int32_t* trace_count) {
+    return sawattn::run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, variant, trace,
+                        trace_count);
 }
 
-int attn_fwd_launch_info(int B, int H, int N, int d, int causal, sawattn_launch_info* out) {
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_variant* variant,
+                         sawattn_launch_info* out) {
     (void)causal;
     if (!out) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "out must be non-null");
     int rc = sawattn::check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
-    sawattn::fill_info(sawattn::make_schedule(B * H, N), d, out);
+    sawattn::Schedule s;
+    rc = sawattn::schedule_for(B, H, N, variant, &s);
+    if (rc != SAWATTN_OK) return rc;
+    sawattn::fill_info(s, d, out);
     return SAWATTN_OK;
 }
 
-int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int32_t* trace, int32_t* trace_count) {
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const sawattn_variant* variant,
+                  int32_t* trace, int32_t* trace_count) {
     using namespace sawattn;
     if (!trace || !trace_count) return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be non-null");
     if (scan_order != SAWATTN_SCAN_CYCLIC && scan_order != SAWATTN_SCAN_SAWTOOTH)
         return fail(SAWATTN_ERR_INVALID_ARG, "scan_order must be SAWATTN_SCAN_CYCLIC or SAWATTN_SCAN_SAWTOOTH");
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
-    const Schedule s = make_schedule(B * H, N);
-    const int grid = kDomains * s.slots, max_local = s.chunks_per_domain * s.rounds_per_chunk;
-    // the kernel's outer loops, one workgroup at a time
-    for (int wg = 0; wg < grid; ++wg) {
-        const int domain = wg % kDomains, slot = wg / kDomains;
+    Schedule s;
+    rc = schedule_for(B, H, N, variant, &s);
+    if (rc != SAWATTN_OK) return rc;
+    // the kernel's outer loop, one workgroup at a time
+    for (int wg = 0; wg < s.grid; ++wg) {
         int local = 0;
-        for (int cs = 0; cs < s.chunks_per_domain; ++cs) {
-            for (int r = 0; r < s.rounds_per_chunk; ++r) {
-                int hh;
-                const int t = decode_tile(s, domain, slot, cs, r, causal != 0, &hh);
-                if (t < 0) continue;
-                const int nkv = visible_kv_tiles(s, t, N, causal != 0);
-                const bool backward = scan_order == SAWATTN_SCAN_SAWTOOTH && (r & 1);
-                int32_t* rec = trace + ((size_t)wg * max_local + local) * 4;
-                rec[0] = hh; rec[1] = t; rec[2] = backward ? nkv - 1 : 0; rec[3] = backward ? 0 : nkv - 1;
-                ++local;
-            }
+        for (int it = 0; it < s.local_iters; ++it) {
+            const Work w = decode_work(s, wg, it, causal != 0, scan_order == SAWATTN_SCAN_SAWTOOTH);
+            if (w.tile < 0) continue;
+            const int nkv = visible_kv_tiles(s, w.tile, N, causal != 0);
+            int32_t* rec = trace + ((size_t)wg * s.local_iters + local) * 4;
+            rec[0] = w.head; rec[1] = w.tile; rec[2] = w.backward ? nkv - 1 : 0; rec[3] = w.backward ? 0 : nkv - 1;
+            ++local;
         }
         trace_count[wg] = local;
     }

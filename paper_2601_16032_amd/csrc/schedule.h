@@ -36,41 +36,117 @@ constexpr int kThreads = 256;    // 4 wavefronts, 32 query rows each
 constexpr int kDomains = 8;      // XCDs
 constexpr int kMaxSlots = 64;    // 32 CUs per XCD x 2 resident workgroups per CU
 
+// Besides that default, the launch variants the paper describes are kept selectable so that they
+// can be measured against it: the literal global stride of Alg. 2 (workgroup k takes the linear
+// indices k, k+G, ... with the tile index fastest, direction = parity of its own iteration count,
+// Alg. 4 as printed), fewer resident workgroups per domain (Sec. 3.4), and the direct launch of
+// Alg. 3 with one workgroup per one or two consecutive query tiles, where the second tile is
+// walked backward (the step-2 alternation of Sec. 4.3).
+enum { kLaunchPersistent = 0, kLaunchGrid = 1 };
+enum { kDecodeDomain = 0, kDecodeLinear = 1 };
+
 struct Schedule {
     int heads;              // B*H
     int q_tiles;            // ceil(N / kTileQ)
     int kv_tiles;           // ceil(N / kTileKV)
-    int parts;              // interleaved subsets per head
-    int slots;              // workgroups per domain
-    int chunks_per_domain;  // heads*parts / kDomains
-    int rounds_per_chunk;   // ceil(ceil(q_tiles/parts) / slots)
+    int launch;             // kLaunchPersistent | kLaunchGrid
+    int decode;             // kDecodeDomain | kDecodeLinear
+    int parts;              // interleaved subsets per head (domain decode; 1 for linear decode)
+    int slots;              // workgroups per domain = grid / kDomains
+    int chunks_per_domain;  // heads*parts / kDomains (domain decode)
+    int rounds_per_chunk;   // persistent, domain decode: ceil(ceil(q_tiles/parts) / slots)
+    int units_per_chunk;    // grid launch, domain decode: workgroups per chunk
+    int tiles_per_wg;       // grid launch: consecutive tiles per workgroup (1 otherwise)
+    int grid;               // workgroups launched (a multiple of kDomains)
+    int local_iters;        // local iterations every workgroup runs through (some may be idle)
+};
+
+struct Work {
+    int head;        // b*H + h
+    int tile;        // query tile index inside the head, -1: nothing to do in this iteration
+    bool backward;   // walk the K/V tiles from the last visible one down to 0
+    bool sync_after; // persistent domain decode: last round of a head that is not the domain's last
 };
 
 SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
+SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-SAW_HD Schedule make_schedule(int heads, int N) {
+// max_slots in 1..kMaxSlots, tiles_per_wg in {1, 2}; the caller has validated them.
+SAW_HD Schedule make_schedule(int heads, int N, int launch = kLaunchPersistent, int decode = kDecodeDomain,
+                              int max_slots = kMaxSlots, int tiles_per_wg = 2) {
     Schedule s;
     s.heads = heads;
     s.q_tiles = (N + kTileQ - 1) / kTileQ;
     s.kv_tiles = (N + kTileKV - 1) / kTileKV;
-    s.parts = kDomains / gcd_i(heads, kDomains);
-    int per_part = (s.q_tiles + s.parts - 1) / s.parts;     // tiles in the largest part
-    s.slots = per_part < kMaxSlots ? per_part : kMaxSlots;
+    s.launch = launch;
+    s.decode = decode;
+    s.tiles_per_wg = launch == kLaunchGrid ? tiles_per_wg : 1;
+    s.parts = decode == kDecodeDomain ? kDomains / gcd_i(heads, kDomains) : 1;
+    const int per_part = (s.q_tiles + s.parts - 1) / s.parts;     // tiles in the largest part
     s.chunks_per_domain = (int)(((long long)heads * s.parts) / kDomains);
-    s.rounds_per_chunk = (per_part + s.slots - 1) / s.slots;
+    s.rounds_per_chunk = 0;
+    s.units_per_chunk = 0;
+    const long long total = (long long)heads * s.q_tiles;
+    if (launch == kLaunchPersistent) {
+        if (decode == kDecodeDomain) {
+            s.slots = per_part < max_slots ? per_part : max_slots;
+            s.rounds_per_chunk = (per_part + s.slots - 1) / s.slots;
+            s.local_iters = s.chunks_per_domain * s.rounds_per_chunk;
+        } else {
+            const int want = ceil_div_i(total, kDomains);
+            s.slots = want < max_slots ? want : max_slots;
+            s.local_iters = ceil_div_i(total, (long long)kDomains * s.slots);
+        }
+    } else {
+        if (decode == kDecodeDomain) {
+            s.units_per_chunk = (per_part + s.tiles_per_wg - 1) / s.tiles_per_wg;
+            s.slots = s.chunks_per_domain * s.units_per_chunk;
+        } else {
+            s.slots = ceil_div_i(ceil_div_i(total, s.tiles_per_wg), kDomains);
+        }
+        s.local_iters = s.tiles_per_wg;
+    }
+    s.grid = kDomains * s.slots;
     return s;
 }
 
-// Tile taken by (domain, slot) in round `r` of the domain's `cs`-th chunk; -1 if it sits out.
-SAW_HD int decode_tile(const Schedule& s, int domain, int slot, int cs, int r, bool causal, int* head) {
-    int c = cs * kDomains + domain;
-    int part = c % s.parts;
-    *head = c / s.parts;
-    int in_part = (s.q_tiles - part + s.parts - 1) / s.parts;
-    int u = r * s.slots + ((r & 1) ? s.slots - 1 - slot : slot);
-    if (u >= in_part) return -1;
-    if (causal) u = in_part - 1 - u;
-    return part + s.parts * u;
+// What workgroup `wg` does in its local iteration `it` (0 <= it < local_iters).
+SAW_HD Work decode_work(const Schedule& s, int wg, int it, bool causal, bool sawtooth) {
+    Work w;
+    w.head = 0;
+    w.tile = -1;
+    w.backward = false;
+    w.sync_after = false;
+    if (s.decode == kDecodeLinear) {
+        // Alg. 2 / Alg. 3 as printed: one linear index over (head, tile), tile fastest.
+        const long long k = s.launch == kLaunchPersistent ? (long long)wg + (long long)it * s.grid
+                                                          : (long long)wg * s.tiles_per_wg + it;
+        if (k < (long long)s.heads * s.q_tiles) {
+            w.head = (int)(k / s.q_tiles);
+            w.tile = (int)(k % s.q_tiles);
+        }
+        w.backward = sawtooth && (it & 1);
+        return w;
+    }
+    const int domain = wg % kDomains, slot = wg / kDomains;
+    int cs, u;
+    if (s.launch == kLaunchPersistent) {
+        cs = it / s.rounds_per_chunk;
+        const int r = it - cs * s.rounds_per_chunk;
+        u = r * s.slots + ((r & 1) ? s.slots - 1 - slot : slot);
+        w.backward = sawtooth && (r & 1);
+        w.sync_after = r + 1 == s.rounds_per_chunk && cs + 1 < s.chunks_per_domain;
+    } else {
+        cs = slot / s.units_per_chunk;
+        u = (slot - cs * s.units_per_chunk) * s.tiles_per_wg + it;
+        w.backward = sawtooth && (it & 1);
+    }
+    const int c = cs * kDomains + domain;
+    const int part = c % s.parts;
+    w.head = c / s.parts;
+    const int in_part = (s.q_tiles - part + s.parts - 1) / s.parts;
+    if (u < in_part) w.tile = part + s.parts * (causal ? in_part - 1 - u : u);
+    return w;
 }
 
 // K/V tiles visible to query tile t.

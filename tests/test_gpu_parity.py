@@ -243,7 +243,7 @@ def test_device_schedule_matches_oracle(sa, B, H, N, d, causal, order):
     K/V tile it visited; bit-exact against the schedule oracle (Alg. 2 + Alg. 4 per cache domain)."""
     from oracle import schedule_oracle as so
     Q, K, V = workloads.make_random(B, H, N, d, "f16", seed=21, device="cuda")
-    O, trace, count = sa.attn_fwd_trace(Q, K, V, scale=0.1, causal=causal, scan_order=order)
+    O, trace, count = sa.attn_fwd_variant(Q, K, V, scale=0.1, causal=causal, scan_order=order, trace=True)
     O2 = sa.attn_fwd(Q, K, V, scale=0.1, causal=causal, scan_order=order)
     torch.cuda.synchronize()
     assert torch.equal(O, O2)                      # recording the schedule does not change the result
@@ -253,3 +253,50 @@ def test_device_schedule_matches_oracle(sa, B, H, N, d, causal, order):
     for wg, recs in want.items():
         got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
         assert got == recs, f"workgroup {wg}"
+
+
+# ------------------------------------------------------------------ launch variants (Alg. 2 as printed, Alg. 3, fewer slots)
+VARIANTS = [dict(decode="linear"), dict(launch="grid"), dict(launch="grid", tiles_per_workgroup=1),
+            dict(launch="grid", decode="linear"), dict(slots_per_domain=3), dict(decode="linear", slots_per_domain=7)]
+
+
+@pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
+@pytest.mark.parametrize("causal", [False, True])
+def test_variants_schedule_and_output(sa, oracle, kw, causal):
+    """Each variant runs the schedule its oracle lists (bit-exact records), gives the default
+    schedule's output bit for bit under the cyclic order (same tiles, same direction, other
+    workgroups), and stays within tolerance of the fp64 oracle under the sawtooth order."""
+    from oracle import schedule_oracle as so
+    var = sa.variant(**kw)
+    for (B, H, N, d, dtype) in [(1, 8, 128 * 21 + 50, 64, "f16"), (2, 3, 700, 128, "bf16")]:
+        Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=55 + N, device="cuda")
+        scale = 1.0 / math.sqrt(d)
+        base = sa.attn_fwd(Q, K, V, scale=scale, causal=causal, scan_order="cyclic", o_dtype=torch.float32)
+        want_O = oracle.attention(Q.cpu(), K.cpu(), V.cpu(), scale, causal=causal)
+        for order in ORDERS:
+            O, trace, count = sa.attn_fwd_variant(Q, K, V, scale=scale, causal=causal, scan_order=order,
+                                                  o_dtype=torch.float32, variant=var, trace=True)
+            torch.cuda.synchronize()
+            want = so.schedule(B, H, N, causal, order, **kw)
+            trace, count = trace.cpu(), count.cpu()
+            assert trace.shape[0] == len(want)
+            for wg, recs in want.items():
+                got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
+                assert got == recs, f"workgroup {wg} {order}"
+            if order == "cyclic":
+                assert torch.equal(O, base)
+            assert_close(O.double().cpu().numpy(), want_O, f"variant {kw} {order} causal={causal} N={N}")
+
+
+def test_variants_at_full_size_agree_with_default(sa):
+    """Workload 4's shape under every variant: cyclic bit-identical to the default, sawtooth within
+    the summation-order difference."""
+    w = workloads.WORKLOADS[4]
+    Q, K, V = workloads.make_qkv(w, device="cuda")
+    base = sa.attn_fwd(Q, K, V, scale=w.scale, causal=False, scan_order="cyclic")
+    for kw in VARIANTS:
+        var = sa.variant(**kw)
+        O = sa.attn_fwd_variant(Q, K, V, scale=w.scale, causal=False, scan_order="cyclic", variant=var)
+        assert torch.equal(O, base), kw
+        O = sa.attn_fwd_variant(Q, K, V, scale=w.scale, causal=False, scan_order="sawtooth", variant=var)
+        print(kw, assert_close(O.double().cpu().numpy(), base.double().cpu().numpy(), f"variant {kw}"))

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol(sa):
     header = open(os.path.join(ROOT, "include", "sawattn.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", header)
-    assert set(names) >= {"attn_fwd", "attn_fwd_trace", "attn_fwd_launch_info", "attn_fwd_plan",
+    assert set(names) >= {"attn_fwd", "attn_fwd_variant", "attn_fwd_launch_info", "attn_fwd_plan",
                           "sawattn_mfma_probe", "sawattn_last_error", "sawattn_version"}
     L = sa.lib()
     for n in names:
@@ -95,6 +95,45 @@ def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
         assert all(r[2] == 0 for r in cyc[wg])
 
 
+VARIANTS = [dict(decode="linear"), dict(launch="grid"), dict(launch="grid", tiles_per_workgroup=1),
+            dict(launch="grid", decode="linear"), dict(launch="grid", decode="linear", tiles_per_workgroup=1),
+            dict(slots_per_domain=1), dict(slots_per_domain=5), dict(decode="linear", slots_per_domain=7)]
+
+
+@pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N", SHAPES)
+def test_schedule_oracle_variants_cover_every_tile_once(B, H, N, causal, kw):
+    sched = so.schedule(B, H, N, causal, "sawtooth", **kw)
+    geo = so.launch_geometry(B, H, N, **kw)
+    assert len(sched) == geo["grid"] and geo["grid"] % 8 == 0
+    seen = set()
+    for wg, recs in sched.items():
+        assert len(recs) <= geo["max_local"]
+        for i, (head, t, first, last) in enumerate(recs):
+            assert (head, t) not in seen
+            seen.add((head, t))
+            n_kv = -(-min((t + 1) * 128, N) // 64) if causal else -(-N // 64)
+            assert {first, last} == {0, n_kv - 1}
+            if kw.get("launch") == "grid" or kw.get("decode") == "linear":
+                assert (first > last) == (i % 2 == 1 and n_kv > 1)     # own iteration parity
+            if kw.get("decode", "domain") == "domain":
+                assert wg % 8 == (head * geo["parts"] + t % geo["parts"]) % 8
+    assert seen == {(h, t) for h in range(B * H) for t in range(geo["q_tiles"])}
+    if "slots_per_domain" in kw:
+        assert geo["slots"] <= kw["slots_per_domain"]
+
+
+def test_schedule_oracle_linear_stride_by_hand():
+    """Printed Alg. 2 on 3 heads x 5 tiles (N = 640) with G = 8: workgroup 1 takes linear indices
+    1 and 9, i.e. (head 0, tile 1) forward and (head 1, tile 4) backward; workgroup 7 takes 7 only."""
+    s = so.schedule(1, 3, 640, False, "sawtooth", decode="linear", slots_per_domain=1)
+    assert s[1] == [(0, 1, 0, 9), (1, 4, 9, 0)]
+    assert s[7] == [(1, 2, 0, 9)]
+    g = so.schedule(1, 3, 640, True, "sawtooth", launch="grid", decode="linear")
+    assert g[2] == [(0, 4, 0, 9), (1, 0, 1, 0)]              # indices 4, 5: last tile of head 0, first of head 1
+
+
 def test_schedule_oracle_hand_example():
     """B*H = 8, N = 128*130: one head per domain, 64 slots, 3 rounds (64 + 64 + 2 tiles).
     Slot 5 of domain 3: round 0 -> tile 5 forward; round 1 (reverse hand-out) -> tile 64 + 58
@@ -119,6 +158,31 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
     for wg in range(info["grid"]):
         got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
         assert got == want[wg], f"workgroup {wg}"
+
+
+@pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N", SHAPES)
+def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
+    var = sa.variant(**kw)
+    info = sa.attn_fwd_launch_info(B, H, N, 64, causal, var)
+    geo = so.launch_geometry(B, H, N, **kw)
+    assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
+    assert info["max_local_tiles"] == geo["max_local"]
+    for order in ("cyclic", "sawtooth"):
+        trace, count = sa.attn_fwd_plan(B, H, N, 64, causal, order, var)
+        want = so.schedule(B, H, N, causal, order, **kw)
+        for wg in range(info["grid"]):
+            got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
+            assert got == want[wg], f"workgroup {wg} {order}"
+
+
+def test_variant_fields_are_validated(sa):
+    for bad in (dict(launch=2), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
+                dict(tiles_per_workgroup=3)):
+        with pytest.raises(binding.SawattnError) as e:
+            sa.attn_fwd_launch_info(1, 8, 2048, 64, False, sa.variant(**bad))
+        assert e.value.code == binding.ERR_INVALID_ARG and "variant." in str(e.value)
 
 
 # ------------------------------------------------------------------ traffic model vs the paper's counters
