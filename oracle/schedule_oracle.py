@@ -11,8 +11,9 @@ domain.
     its tiles (parts = 8 / gcd(B*H, 8)); chunk c = head*parts + part belongs to domain c mod 8 and
     the chunks of a domain are processed in increasing c.
   * The `slots` workgroups of a domain stride over a chunk's tile list with stride `slots`
-    (Alg. 2 with G = slots); one pass of all slots is a round.  Odd rounds hand the tiles out in
-    reverse slot order; causal chunks list their tiles from the longest to the shortest.
+    (Alg. 2 with G = slots); one pass of all slots is a round.  Rounds are numbered through all
+    chunks of the domain and the odd ones hand the tiles out in reverse slot order; causal chunks
+    list their tiles from the longest to the shortest.
   * Scan direction (Alg. 4): forward on even rounds, backward on odd rounds, the round count
     restarting with every chunk (a new chunk brings new K/V, so there is nothing to re-use by
     walking backward into it); N_KV is the number of K/V tiles visible to the query tile.
@@ -116,9 +117,10 @@ def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str 
             continue
         for slot in range(slots):
             recs = []
-            for head, tiles in chunk_tiles:
+            for n_chunk, (head, tiles) in enumerate(chunk_tiles):
                 for r in range(geo["rounds_per_chunk"]):
-                    hand_out = list(range(slots)) if r % 2 == 0 else list(range(slots - 1, -1, -1))
+                    nth_round = n_chunk * geo["rounds_per_chunk"] + r
+                    hand_out = list(range(slots)) if nth_round % 2 == 0 else list(range(slots - 1, -1, -1))
                     pos = r * slots + hand_out.index(slot)
                     if pos < len(tiles):
                         recs.append(record(head, tiles[pos], N, causal, saw and r % 2 == 1))

@@ -931,8 +931,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
         }
         configured = true;
     }
-    if (p.sched.launch == kLaunchPersistent && p.sched.decode == kDecodeDomain && p.sched.chunks_per_domain > 1)
-        hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream);
+    if (p.sched.sync_heads) hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), Geo<D>::kLdsBytes, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -944,7 +943,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 }
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
-int schedule_for(int B, int H, int N, const sawattn_variant* v, Schedule* out) {
+int schedule_for(int B, int H, int N, bool causal, const sawattn_variant* v, Schedule* out) {
     int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = kMaxSlots, tiles_per_wg = 2;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
@@ -960,7 +959,7 @@ int schedule_for(int B, int H, int N, const sawattn_variant* v, Schedule* out) {
         if (v->slots_per_domain) max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
     }
-    *out = make_schedule(B * H, N, launch, decode, max_slots, tiles_per_wg);
+    *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg);
     return SAWATTN_OK;
 }
 
@@ -970,7 +969,7 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     Schedule sched;
-    rc = schedule_for(B, H, N, variant, &sched);
+    rc = schedule_for(B, H, N, causal != 0, variant, &sched);
     if (rc != SAWATTN_OK) return rc;
     if (!Q || !K || !V || !O) return fail(SAWATTN_ERR_INVALID_ARG, "Q, K, V and O must be non-null");
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u)
@@ -1034,12 +1033,11 @@ int attn_fwd_variant(const void* Q, const void* K, const void* V, void* O, int B
 
 int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_variant* variant,
                          sawattn_launch_info* out) {
-    (void)causal;
     if (!out) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "out must be non-null");
     int rc = sawattn::check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     sawattn::Schedule s;
-    rc = sawattn::schedule_for(B, H, N, variant, &s);
+    rc = sawattn::schedule_for(B, H, N, causal != 0, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     sawattn::fill_info(s, d, out);
     return SAWATTN_OK;
@@ -1054,7 +1052,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const 
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     Schedule s;
-    rc = schedule_for(B, H, N, variant, &s);
+    rc = schedule_for(B, H, N, causal != 0, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     // the kernel's outer loop, one workgroup at a time
     for (int wg = 0; wg < s.grid; ++wg) {

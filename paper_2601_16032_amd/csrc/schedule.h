@@ -12,8 +12,10 @@
 //     chunks of one domain run one after another;
 //   * inside a chunk the `slots` workgroups of the domain take its tiles in rounds of `slots`
 //     consecutive tiles, so all of them stream the same head's K/V at the same time;
-//   * odd rounds hand the tiles out in reverse slot order, which evens out the causal cost
-//     (tile i costs i+1 K/V tiles), and causal chunks start from their longest tile;
+//   * a workgroup's odd local iterations (rounds counted across the chunks of its domain) hand
+//     the tiles out in reverse slot order, which evens out the causal cost (tile i costs i+1 K/V
+//     tiles) inside a head with an even number of rounds and over two heads otherwise; causal
+//     chunks start from their longest tile;
 //   * the scan direction of a round is the parity of the round index inside its chunk: this is
 //     Alg. 4's local-iteration parity restarted at every chunk.  Consecutive rounds of one chunk
 //     walk the same K/V, which is where reversing the direction shortens the reuse distance; the
@@ -59,6 +61,7 @@ struct Schedule {
     int tiles_per_wg;       // grid launch: consecutive tiles per workgroup (1 otherwise)
     int grid;               // workgroups launched (a multiple of kDomains)
     int local_iters;        // local iterations every workgroup runs through (some may be idle)
+    int sync_heads;         // persistent, domain decode: the workgroups of a domain wait for each other between heads
 };
 
 struct Work {
@@ -72,7 +75,7 @@ SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } retu
 SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // max_slots in 1..kMaxSlots, tiles_per_wg in {1, 2}; the caller has validated them.
-SAW_HD Schedule make_schedule(int heads, int N, int launch = kLaunchPersistent, int decode = kDecodeDomain,
+SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch = kLaunchPersistent, int decode = kDecodeDomain,
                               int max_slots = kMaxSlots, int tiles_per_wg = 2) {
     Schedule s;
     s.heads = heads;
@@ -86,12 +89,17 @@ SAW_HD Schedule make_schedule(int heads, int N, int launch = kLaunchPersistent, 
     s.chunks_per_domain = (int)(((long long)heads * s.parts) / kDomains);
     s.rounds_per_chunk = 0;
     s.units_per_chunk = 0;
+    s.sync_heads = 0;
     const long long total = (long long)heads * s.q_tiles;
     if (launch == kLaunchPersistent) {
         if (decode == kDecodeDomain) {
             s.slots = per_part < max_slots ? per_part : max_slots;
             s.rounds_per_chunk = (per_part + s.slots - 1) / s.slots;
             s.local_iters = s.chunks_per_domain * s.rounds_per_chunk;
+            // Waiting for the domain between heads pays only if its workgroups finish a head together:
+            // every slot gets a tile in every round, and causal tiles pair up long with short.
+            const bool even_load = s.q_tiles % (s.parts * s.slots) == 0 && (!causal || s.rounds_per_chunk % 2 == 0);
+            s.sync_heads = even_load && s.chunks_per_domain > 1;
         } else {
             const int want = ceil_div_i(total, kDomains);
             s.slots = want < max_slots ? want : max_slots;
@@ -133,9 +141,9 @@ SAW_HD Work decode_work(const Schedule& s, int wg, int it, bool causal, bool saw
     if (s.launch == kLaunchPersistent) {
         cs = it / s.rounds_per_chunk;
         const int r = it - cs * s.rounds_per_chunk;
-        u = r * s.slots + ((r & 1) ? s.slots - 1 - slot : slot);
+        u = r * s.slots + ((it & 1) ? s.slots - 1 - slot : slot);
         w.backward = sawtooth && (r & 1);
-        w.sync_after = r + 1 == s.rounds_per_chunk && cs + 1 < s.chunks_per_domain;
+        w.sync_after = s.sync_heads && r + 1 == s.rounds_per_chunk && cs + 1 < s.chunks_per_domain;
     } else {
         cs = slot / s.units_per_chunk;
         u = (slot - cs * s.units_per_chunk) * s.tiles_per_wg + it;

@@ -134,6 +134,18 @@ def test_schedule_oracle_linear_stride_by_hand():
     assert g[2] == [(0, 4, 0, 9), (1, 0, 1, 0)]              # indices 4, 5: last tile of head 0, first of head 1
 
 
+@pytest.mark.parametrize("B,H,N,causal", [(1, 8, 2048, False), (1, 16, 8192, True), (1, 32, 16384, False),
+                                          (4, 32, 32768, True)])
+def test_schedule_gives_every_workgroup_the_same_number_of_tile_steps(sa, B, H, N, causal):
+    """On the benchmark shapes every workgroup walks the same number of K/V tiles in total: causal
+    tiles (tile i costs i+1) are paired long with short inside a head when it has an even number
+    of rounds, across two heads when it has one round (workload 3)."""
+    trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, "sawtooth")
+    cost = [sum(abs(int(a) - int(b)) + 1 for (_, _, a, b) in trace[wg, : int(count[wg])].tolist())
+            for wg in range(trace.shape[0])]
+    assert max(cost) == min(cost)
+
+
 def test_schedule_oracle_hand_example():
     """B*H = 8, N = 128*130: one head per domain, 64 slots, 3 rounds (64 + 64 + 2 tiles).
     Slot 5 of domain 3: round 0 -> tile 5 forward; round 1 (reverse hand-out) -> tile 64 + 58
