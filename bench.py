@@ -29,14 +29,14 @@ MFMA_PEAK_TFLOPS_16BIT = 2500.0   # MI355X dense fp16/bf16 matrix peak
 MEASURED_TRAFFIC_BYTES: dict = {
     (4, "sawtooth"): 1.0242e9, (4, "cyclic"): 1.1413e9,      # profiles/attn_fwd_cfg4_*.txt
     (5, "sawtooth"): 1.1207e10, (5, "cyclic"): 1.3875e10,    # profiles/attn_fwd_cfg5_*.txt
-    (3, "sawtooth"): 1.6841e8, (3, "cyclic"): 1.6840e8,      # profiles/attn_fwd_cfg3_*.txt
+    (3, "sawtooth"): 1.7100e8, (3, "cyclic"): 1.7101e8,      # profiles/attn_fwd_cfg3_*.txt
     (2, "sawtooth"): 8.6106e6, (2, "cyclic"): 8.6106e6,      # profiles/attn_fwd_cfg2_*.txt
 }
 # TCC (L2) miss requests per launch from `rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum`.
 MEASURED_TCC_MISS: dict = {
     (4, "sawtooth"): 7.999e6, (4, "cyclic"): 8.913e6,
     (5, "sawtooth"): 8.753e7, (5, "cyclic"): 1.0825e8,
-    (3, "sawtooth"): 1.3127e6, (3, "cyclic"): 1.3127e6,
+    (3, "sawtooth"): 1.3344e6, (3, "cyclic"): 1.3344e6,
 }
 
 
@@ -85,13 +85,13 @@ def time_order(sa, torch, Q, K, V, O, w, order, steps, warmup, evict_buf=None):
 def mfma_probe(sa, torch):
     """Matrix rate this chip sustains (context for roofline.frac, which uses the datasheet peak)."""
     res = {"unit": "TFLOP/s"}
-    for mode, key in ((0, "registers_fixed_operands"), (1, "lds_fed_random_operands")):
-        for _ in range(2):
-            sa.sawattn_mfma_probe(2000, mode)
+    for mode, key in ((0, "zero_operands"), (1, "live_operands_in_registers"), (2, "live_operands_lds_fed")):
+        for _ in range(10):                      # some tens of milliseconds: the clock settles
+            sa.sawattn_mfma_probe(4000, mode)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        flops = sum(sa.sawattn_mfma_probe(4000, mode) for _ in range(5))
+        flops = sum(sa.sawattn_mfma_probe(4000, mode) for _ in range(10))
         e1.record()
         torch.cuda.synchronize()
         res[key] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -164,8 +164,10 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const 
  *
  *   sink       device, >= 512 floats; never written in practice (keeps the work alive).
  *   iters      > 0.
- *   mode       0: operands fixed in registers;  1: A operands re-read from an LDS tile of
- *              pseudo-random values with the attention kernel's K-operand pattern.
+ *   mode       0: all operands zero (no switching in the multipliers: the datasheet condition);
+ *              1: operands in registers with values distributed like attention inputs;
+ *              2: as 1, with the A operands re-read from an LDS tile with the attention kernel's
+ *                 K-operand pattern.  The chip is power limited: 1 and 2 run far below 0.
  *   hip_stream stream to launch on (NULL = default); returns without waiting.
  *   flops_out  host, optional: receives the flop count of the launch (2*32*32*16 per MFMA).
  * Errors: INVALID_ARG, RUNTIME.

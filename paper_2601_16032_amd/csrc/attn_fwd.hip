@@ -838,23 +838,44 @@ __global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
 // ------------------------------------------------------------------------------- sustained-rate probe
 // What the matrix pipes of this chip sustain, to put the datasheet peak into context: every
 // wavefront runs `iters` x 16 v_mfma_f32_32x32x16_f16 on four independent accumulators.
-//   mode 0: operands fixed in registers (least switching activity, highest clock);
-//   mode 1: A operands re-read from an LDS tile of pseudo-random binary16 values with the K-operand
-//           access pattern of the attention kernel, one ds_read_b128 per MFMA: the best any kernel
-//           that feeds 32-row operands from LDS with live data can reach.
-// The chip lowers its clock with matrix activity, so the two differ markedly.
+//   mode 0: all operands zero.  Nothing switches in the multipliers, the chip holds its peak clock
+//           and the rate is the datasheet's.
+//   mode 1: operands in registers holding values distributed like attention inputs (about
+//           0.5 x standard normal); A cycles through four registers, B through four.
+//   mode 2: as mode 1 with the A operands re-read from an LDS tile with the K-operand access
+//           pattern of the attention kernel, one ds_read_b128 per MFMA.
+// The chip is power limited and lowers its clock with switching activity, so the rate with live
+// data is far below the rate with zeros, whatever the instruction stream does besides.
+__device__ __forceinline__ unsigned probe_hash(unsigned x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+// Two binary16 values, each about 0.5 x standard normal (sum of four uniforms, centred and scaled).
+__device__ __forceinline__ unsigned probe_pair(unsigned seed) {
+    h2 v;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const unsigned r = probe_hash(seed * 2u + k + 1u);
+        const float u = (float)(r & 255u) + (float)((r >> 8) & 255u) + (float)((r >> 16) & 255u) + (float)(r >> 24);
+        v[k] = (_Float16)((u - 510.0f) * (0.5f / 147.8f));
+    }
+    return __builtin_bit_cast(unsigned, v);
+}
+
 __global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters, int mode) {
     __shared__ __align__(16) char tile[16384];
     LDS_PTR(char) lds = (LDS_PTR(char))tile;
-    for (int i = threadIdx.x; i < 16384 / 4; i += blockDim.x) {
-        const unsigned hsh = (i * 2654435761u) ^ ((i >> 3) * 40503u);
-        ((LDS_PTR(unsigned))lds)[i] = (hsh & 0x83ff83ffu) | 0x38003800u;   // binary16 pairs with |x| in [0.5, 1)
-    }
+    for (int i = threadIdx.x; i < 16384 / 4; i += blockDim.x) ((LDS_PTR(unsigned))lds)[i] = probe_pair(i);
     __syncthreads();
     const int lane = threadIdx.x & 63, g = lane >> 5, ln = lane & 31;
-    u4 b;
+    u4 a4[4], b4[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) b[e] = 0x38003c00u + ((threadIdx.x * 37u + e * 11u) % 97u) * 0x00010003u;
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            a4[q][e] = mode == 0 ? 0u : probe_pair(100000u + threadIdx.x * 32u + q * 4u + e);
+            b4[q][e] = mode == 0 ? 0u : probe_pair(900000u + threadIdx.x * 32u + q * 4u + e);
+        }
     f16v c[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -863,11 +884,10 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters,
     unsigned addr[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) addr[ks] = (unsigned)(size_t)lds + ln * 256 + ((2 * ks + g) ^ Geo<128>::swz(ln)) * 16;
-    if (mode == 0) {
-        const u4 a = *(LDS_PTR(u4))(size_t)addr[0];
+    if (mode != 2) {
         for (int i = 0; i < iters; ++i) {
 #pragma unroll
-            for (int t = 0; t < 16; ++t) c[t & 3] = mfma_16bit<false>(a, b, c[t & 3]);
+            for (int t = 0; t < 16; ++t) c[t & 3] = mfma_16bit<false>(a4[t & 3], b4[(t >> 2) & 3], c[t & 3]);
         }
     } else {
         for (int i = 0; i < iters; ++i) {
@@ -877,7 +897,7 @@ __global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters,
 #pragma unroll
             for (int t = 0; t < 16; ++t) {
                 if (t + 2 < 16) a[t + 2] = *(LDS_PTR(u4))(size_t)(addr[(t + 2) / 2] + ((t + 2) & 1) * 8192);
-                c[t & 3] = mfma_16bit<false>(a[t], b, c[t & 3]);
+                c[t & 3] = mfma_16bit<false>(a[t], b4[(t >> 2) & 3], c[t & 3]);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1072,7 +1092,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const 
 
 int sawattn_mfma_probe(float* sink, int iters, int mode, void* hip_stream, double* flops_out) {
     using namespace sawattn;
-    if (!sink || iters <= 0 || (mode != 0 && mode != 1)) return fail(SAWATTN_ERR_INVALID_ARG, "sink non-null, iters > 0, mode 0 or 1");
+    if (!sink || iters <= 0 || mode < 0 || mode > 2) return fail(SAWATTN_ERR_INVALID_ARG, "sink non-null, iters > 0, mode 0, 1 or 2");
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
         (void)hipGetLastError();
