@@ -91,9 +91,9 @@ enum {
 typedef struct sawattn_variant {
     int launch;              /* SAWATTN_LAUNCH_* */
     int decode;              /* SAWATTN_DECODE_* */
-    int slots_per_domain;    /* persistent launch: at most this many workgroups per XCD (1..64), so
-                                G = 8 * slots (Sec. 3.4's resident-CTA sweep); 0 = default (64).
-                                Ignored by the grid launch. */
+    int slots_per_domain;    /* persistent launch: at most this many workgroups per XCD, so G = 8 * slots
+                                (Sec. 3.4's resident-CTA sweep): 1..64, or 1..96 for d = 64, where three
+                                workgroups fit a CU; 0 = default (that maximum).  Ignored by the grid launch. */
     int tiles_per_workgroup; /* grid launch: 1, or 2 = forward over the first tile and, with the sawtooth
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
                                 0 = default (2).  Ignored by the persistent launch. */

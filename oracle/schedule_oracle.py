@@ -34,7 +34,12 @@ from __future__ import annotations
 
 from math import gcd
 
-T_Q, T_KV, DOMAINS, MAX_SLOTS = 128, 64, 8, 64
+T_Q, T_KV, DOMAINS = 128, 64, 8
+
+
+def resident_slots(d: int) -> int:
+    """Workgroups of one domain that run at the same time: 32 CUs x 3 per CU at d = 64, x 2 at d = 128."""
+    return 96 if d == 64 else 64
 
 
 def ceil_div(a: int, b: int) -> int:
@@ -42,7 +47,8 @@ def ceil_div(a: int, b: int) -> int:
 
 
 def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",
-                    slots_per_domain: int = MAX_SLOTS, tiles_per_workgroup: int = 2):
+                    slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128):
+    slots_per_domain = slots_per_domain or resident_slots(d)
     heads = B * H
     q_tiles = ceil_div(N, T_Q)
     total = heads * q_tiles
@@ -83,10 +89,10 @@ def record(head: int, t: int, N: int, causal: bool, backward: bool):
 
 
 def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str = "persistent",
-             decode: str = "domain", slots_per_domain: int = MAX_SLOTS, tiles_per_workgroup: int = 2):
+             decode: str = "domain", slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128):
     """Return {workgroup: [(head, query tile, first K/V tile, last K/V tile), ...]} in the order
     each workgroup processes its tiles."""
-    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup)
+    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d)
     heads, parts, slots, grid = B * H, geo["parts"], geo["slots"], geo["grid"]
     saw = scan_order == "sawtooth"
     out = {}

@@ -802,7 +802,7 @@ __device__ __forceinline__ void domain_sync(int domain, int slots) {
 }
 
 template <int D, bool BF16, bool CAUSAL>
-__global__ __launch_bounds__(kThreads, 2) void attn_fwd_kernel(Params p) {
+__global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void attn_fwd_kernel(Params p) {
     extern __shared__ __align__(16) char smem[];
     const Schedule& s = p.sched;
     const int lane0 = threadIdx.x & 63;
@@ -963,15 +963,15 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 }
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
-int schedule_for(int B, int H, int N, bool causal, const sawattn_variant* v, Schedule* out) {
-    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = kMaxSlots, tiles_per_wg = 2;
+int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant* v, Schedule* out) {
+    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = resident_slots(d), tiles_per_wg = 2;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
         if (v->decode != SAWATTN_DECODE_DOMAIN && v->decode != SAWATTN_DECODE_LINEAR)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.decode must be SAWATTN_DECODE_DOMAIN or SAWATTN_DECODE_LINEAR");
-        if (v->slots_per_domain < 0 || v->slots_per_domain > kMaxSlots)
-            return fail(SAWATTN_ERR_INVALID_ARG, "variant.slots_per_domain must be 0 (default) or 1..64");
+        if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d))
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64)");
         if (v->tiles_per_workgroup < 0 || v->tiles_per_workgroup > 2)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.tiles_per_workgroup must be 0 (default), 1 or 2");
         launch = v->launch == SAWATTN_LAUNCH_GRID ? kLaunchGrid : kLaunchPersistent;
@@ -989,7 +989,7 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     Schedule sched;
-    rc = schedule_for(B, H, N, causal != 0, variant, &sched);
+    rc = schedule_for(B, H, N, d, causal != 0, variant, &sched);
     if (rc != SAWATTN_OK) return rc;
     if (!Q || !K || !V || !O) return fail(SAWATTN_ERR_INVALID_ARG, "Q, K, V and O must be non-null");
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u)
@@ -1057,7 +1057,7 @@ int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_v
     int rc = sawattn::check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     sawattn::Schedule s;
-    rc = sawattn::schedule_for(B, H, N, causal != 0, variant, &s);
+    rc = sawattn::schedule_for(B, H, N, d, causal != 0, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     sawattn::fill_info(s, d, out);
     return SAWATTN_OK;
@@ -1072,7 +1072,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const 
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     Schedule s;
-    rc = schedule_for(B, H, N, causal != 0, variant, &s);
+    rc = schedule_for(B, H, N, d, causal != 0, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     // the kernel's outer loop, one workgroup at a time
     for (int wg = 0; wg < s.grid; ++wg) {

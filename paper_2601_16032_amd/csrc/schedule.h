@@ -36,7 +36,11 @@ constexpr int kTileQ = 128;      // query rows per workgroup tile
 constexpr int kTileKV = 64;      // key/value rows per streamed tile
 constexpr int kThreads = 256;    // 4 wavefronts, 32 query rows each
 constexpr int kDomains = 8;      // XCDs
-constexpr int kMaxSlots = 64;    // 32 CUs per XCD x 2 resident workgroups per CU
+constexpr int kMaxSlots = 96;    // largest number of workgroups per domain for any head dimension
+
+// Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
+// dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for two.
+SAW_HD int resident_slots(int d) { return d == 64 ? 96 : 64; }
 
 // Besides that default, the launch variants the paper describes are kept selectable so that they
 // can be measured against it: the literal global stride of Alg. 2 (workgroup k takes the linear
@@ -74,9 +78,8 @@ struct Work {
 SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
 SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-// max_slots in 1..kMaxSlots, tiles_per_wg in {1, 2}; the caller has validated them.
-SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch = kLaunchPersistent, int decode = kDecodeDomain,
-                              int max_slots = kMaxSlots, int tiles_per_wg = 2) {
+// max_slots in 1..resident_slots(d), tiles_per_wg in {1, 2}; the caller has validated them.
+SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int decode, int max_slots, int tiles_per_wg) {
     Schedule s;
     s.heads = heads;
     s.q_tiles = (N + kTileQ - 1) / kTileQ;

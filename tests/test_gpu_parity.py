@@ -66,12 +66,12 @@ def test_ragged_lengths(sa, oracle, d, dtype, causal):
 def test_many_rounds_and_heads(sa, oracle, causal):
     """More query tiles than resident workgroups of a domain (several rounds, both directions) and
     more heads than domains (several chunks per domain)."""
-    Q, K, V = workloads.make_random(1, 8, 128 * 70, 64, "f16", seed=77)   # 70 tiles per head: 2 rounds
-    rows = list(range(0, 128 * 70, 131)) + [128 * 70 - 1]
+    Q, K, V = workloads.make_random(1, 8, 128 * 100, 64, "f16", seed=77)   # 100 tiles per head: 2 rounds of 96
+    rows = list(range(0, 128 * 100, 131)) + [128 * 100 - 1]
     want = oracle.attention(Q, K, V, 0.125, causal=causal, rows=rows)
     for order in ORDERS:
         got = run_gpu(sa, Q, K, V, 0.125, causal, order, o_dtype=torch.float32)[:, :, rows]
-        assert_close(got, want, f"70 tiles causal={causal} {order}")
+        assert_close(got, want, f"100 tiles causal={causal} {order}")
     Q, K, V = workloads.make_random(3, 7, 300, 128, "bf16", seed=78)      # 21 heads, parts = 8
     want = oracle.attention(Q, K, V, 0.09, causal=causal)
     for order in ORDERS:
@@ -120,7 +120,7 @@ def test_moving_maximum_in_both_directions(sa, oracle, dtype, d):
     """Scores whose level changes from K/V tile to K/V tile by far more than the slack the kernel
     allows before it rescales (Alg. 1's running maximum has to be raised again and again), on a
     shape with two rounds per head so that the same rows' neighbours are scanned in both directions."""
-    H, N = 8, 128 * 70
+    H, N = 8, 128 * 100
     g = torch.Generator("cpu").manual_seed(4242 + d)
     level = 60.0 * torch.rand(H, N // 64, generator=g)                 # per 64-key tile
     level[:, 5] = 75.0                                                 # a clear winner somewhere early
@@ -237,7 +237,8 @@ def test_scan_orders_agree_small(sa, cfg):
 # ------------------------------------------------------------------ work decode and scan direction
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("B,H,N,d", [(1, 8, 128 * 70, 64), (2, 3, 333, 128), (1, 32, 4096, 128), (1, 1, 256, 64)])
+@pytest.mark.parametrize("B,H,N,d", [(1, 8, 128 * 70, 128), (1, 8, 128 * 100, 64), (2, 3, 333, 128), (1, 32, 4096, 128),
+                                     (1, 1, 256, 64)])
 def test_device_schedule_matches_oracle(sa, B, H, N, d, causal, order):
     """Every workgroup records the query tile it took at each local iteration and the first / last
     K/V tile it visited; bit-exact against the schedule oracle (Alg. 2 + Alg. 4 per cache domain)."""
@@ -247,7 +248,7 @@ def test_device_schedule_matches_oracle(sa, B, H, N, d, causal, order):
     O2 = sa.attn_fwd(Q, K, V, scale=0.1, causal=causal, scan_order=order)
     torch.cuda.synchronize()
     assert torch.equal(O, O2)                      # recording the schedule does not change the result
-    want = so.schedule(B, H, N, causal, order)
+    want = so.schedule(B, H, N, causal, order, d=d)
     trace, count = trace.cpu(), count.cpu()
     assert trace.shape[0] == len(want)
     for wg, recs in want.items():
@@ -277,7 +278,7 @@ def test_variants_schedule_and_output(sa, oracle, kw, causal):
             O, trace, count = sa.attn_fwd_variant(Q, K, V, scale=scale, causal=causal, scan_order=order,
                                                   o_dtype=torch.float32, variant=var, trace=True)
             torch.cuda.synchronize()
-            want = so.schedule(B, H, N, causal, order, **kw)
+            want = so.schedule(B, H, N, causal, order, d=d, **kw)
             trace, count = trace.cpu(), count.cpu()
             assert trace.shape[0] == len(want)
             for wg, recs in want.items():

@@ -161,15 +161,16 @@ def test_schedule_oracle_hand_example():
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
-    info = sa.attn_fwd_launch_info(B, H, N, 128, causal)
-    geo = so.launch_geometry(B, H, N)
-    assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
-    assert info["parts_per_head"] == geo["parts"] and info["q_tiles_per_head"] == geo["q_tiles"]
-    trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, order)
-    want = so.schedule(B, H, N, causal, order)
-    for wg in range(info["grid"]):
-        got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
-        assert got == want[wg], f"workgroup {wg}"
+    for d in (128, 64):                      # d = 64 runs up to 96 workgroups per domain, d = 128 up to 64
+        info = sa.attn_fwd_launch_info(B, H, N, d, causal)
+        geo = so.launch_geometry(B, H, N, d=d)
+        assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
+        assert info["parts_per_head"] == geo["parts"] and info["q_tiles_per_head"] == geo["q_tiles"]
+        trace, count = sa.attn_fwd_plan(B, H, N, d, causal, order)
+        want = so.schedule(B, H, N, causal, order, d=d)
+        for wg in range(info["grid"]):
+            got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
+            assert got == want[wg], f"workgroup {wg} d={d}"
 
 
 @pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
@@ -178,12 +179,12 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
 def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
     var = sa.variant(**kw)
     info = sa.attn_fwd_launch_info(B, H, N, 64, causal, var)
-    geo = so.launch_geometry(B, H, N, **kw)
+    geo = so.launch_geometry(B, H, N, d=64, **kw)
     assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
     assert info["max_local_tiles"] == geo["max_local"]
     for order in ("cyclic", "sawtooth"):
         trace, count = sa.attn_fwd_plan(B, H, N, 64, causal, order, var)
-        want = so.schedule(B, H, N, causal, order, **kw)
+        want = so.schedule(B, H, N, causal, order, d=64, **kw)
         for wg in range(info["grid"]):
             got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
             assert got == want[wg], f"workgroup {wg} {order}"
@@ -193,8 +194,11 @@ def test_variant_fields_are_validated(sa):
     for bad in (dict(launch=2), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
                 dict(tiles_per_workgroup=3)):
         with pytest.raises(binding.SawattnError) as e:
-            sa.attn_fwd_launch_info(1, 8, 2048, 64, False, sa.variant(**bad))
+            sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(**bad))
         assert e.value.code == binding.ERR_INVALID_ARG and "variant." in str(e.value)
+    assert sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=96))["slots"] == 96
+    with pytest.raises(binding.SawattnError):
+        sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=97))
 
 
 # ------------------------------------------------------------------ traffic model vs the paper's counters
