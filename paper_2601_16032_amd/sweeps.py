@@ -11,7 +11,7 @@ restates.
 Studies
   seqlen    Sec. 3.2 / 3.3: sequence length 2K...128K at B=1, H in {1, 8}, d in {64, 128}:
             L2 requests against 2NdE(1 + N/T_q), and where non-compulsory misses set in.
-  resident  Sec. 3.4: G = 8 w persistent workgroups, w = 1...64 per XCD: hit rate against 1 - 1/w.
+  resident  Sec. 3.4: G = 8 w persistent workgroups, w = 1...64 (96 at d = 64) per XCD: hit rate against 1 - 1/w.
   decode    Sec. 2.2 Alg. 2 as printed (one linear stride over all XCDs) against the per-XCD decode.
   launch    Alg. 3 (direct launch, one or two query tiles per workgroup) against the persistent
             launch, both scan orders (Sec. 4.3's two program variants).
@@ -49,7 +49,7 @@ def study_points(study: str):
                         pts.append(_pt(1, H, N, d, order=order))
     elif study == "resident":
         for (H, N, d) in ((8, 32768, 64), (32, 16384, 128)):
-            for w in (1, 2, 4, 8, 16, 32, 64):
+            for w in (1, 2, 4, 8, 16, 32, 64) + ((96,) if d == 64 else ()):
                 for order in ("cyclic", "sawtooth"):
                     pts.append(_pt(1, H, N, d, order=order, slots_per_domain=w))
     elif study == "decode":
