@@ -97,6 +97,9 @@ typedef struct sawattn_variant {
     int tiles_per_workgroup; /* grid launch: 1, or 2 = forward over the first tile and, with the sawtooth
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
                                 0 = default (2).  Ignored by the persistent launch. */
+    int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
+                                64 (d = 128 only): 256 rows, one workgroup per CU, every K/V fragment read
+                                from LDS feeds two MFMAs; 0 = default (32). */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round

@@ -384,10 +384,10 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 // all without the mask code).  Self-contained: fetches its first tile itself and leaves with every
 // wavefront past the barrier that follows its last tile.  Iteration `it` uses LDS buffer pair it & 1
 // and, while computing, fetches the tile of iteration it+1 into the other pair.
-template <int D, bool BF16, bool CAUSAL, bool MASKED>
-__device__ __forceinline__ void general_range(TileState<D>& st, const LaneMap<D>& lm, const char* Kh, const char* Vh, int N,
-                                              float c, int j_first, int step, int count, int qw0, int qrow,
-                                              bool wave_has_rows, int lane, LDS_PTR(char) lds) {
+template <int D, bool BF16, bool CAUSAL, bool MASKED, int NH>
+__device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const LaneMap<D>& lm, const char* Kh, const char* Vh, int N,
+                                              float c, int j_first, int step, int count, int qw0, int qrow, int lane,
+                                              LDS_PTR(char) lds) {
     using G = Geo<D>;
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
@@ -424,8 +424,11 @@ __device__ __forceinline__ void general_range(TileState<D>& st, const LaneMap<D>
             else tile_to_lds<D>(Vh, j + step, off, lm, lds0 + (2 + (cur ^ 1)) * G::kTile);
         }
         const int kv0 = j * kTileKV;
-        const bool active = wave_has_rows && (!CAUSAL || kv0 <= qw0 + 31);
-        if (active) compute_tile<D, BF16, CAUSAL, MASKED>(st, ra, c, kv0, qrow, lane, N);
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {   // half h: query rows qw0 + 32h .. +31 (this lane: qrow + 32h)
+            const bool active = qw0 + 32 * h < N && (!CAUSAL || kv0 <= qw0 + 32 * h + 31);
+            if (active) compute_tile<D, BF16, CAUSAL, MASKED>(st[h], ra, c, kv0, qrow + 32 * h, lane, N);
+        }
         ra.flip(cur ? -G::kTile : G::kTile);
         if (more) {
             if constexpr (BF16) regs_to_lds_f16<D>(vreg, lm, lane, lds + (2 + (cur ^ 1)) * G::kTile);
@@ -694,13 +697,329 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
     __syncthreads();   // all reads of the last tile are done before anything refills the buffers
 }
 
-// One query tile (Alg. 1 body): rows [t*128, t*128+128) of head `hh`, K/V tiles j0, j0+step, ... (nkv of them).
-template <int D, bool BF16, bool CAUSAL>
+// ------------------------------------------------------------------------------------------------
+// Wide variant (head dimension 128): a wavefront owns 64 query rows as two 32-row halves, a workgroup
+// 256 rows, one workgroup per CU.  Every K and V^T fragment read from LDS feeds two MFMAs, one per
+// half, which halves the LDS operand traffic and the L2 -> LDS traffic per flop; the chip being
+// power limited, that is where the remaining throughput is.  With one wavefront per SIMD there is
+// no second wavefront to hide latencies behind, so K and V are fetched three tiles ahead into four
+// LDS buffers each and a fetch has two whole iterations to land.
+// MFMAs of the wide variant, written out so that the register file of every operand is fixed: with
+// more than 256 registers per wavefront the accumulation registers (AccVGPRs) have to hold what only
+// the matrix pipe touches -- the O^T accumulators and the Q^T fragments -- and nothing the vector ALU
+// reads, or every use costs a copy.  The compiler does not see these as MFMAs and inserts no wait
+// states for them; mfma_settle() is placed wherever the vector ALU reads an accumulator that the
+// few preceding instructions may still be writing (8 passes + 3 wait states).
+template <bool BF16>
+__device__ __forceinline__ void mfma_s_first(f16v& acc, u4 k_frag, const u4& q_frag) {
+    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_frag), "a"(q_frag));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_frag), "a"(q_frag));
+}
+template <bool BF16>
+__device__ __forceinline__ void mfma_s(f16v& acc, u4 k_frag, const u4& q_frag) {
+    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
+}
+__device__ __forceinline__ void mfma_o(f16v& acc, s8 v_frag, const u4& p_frag) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_frag), "v"(p_frag));
+}
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
+
+constexpr int kWideBuffers = 4;
+constexpr int kWideLdsBytes = 2 * kWideBuffers * Geo<128>::kTile;
+
+template <bool BF16>
+__device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], const LaneMap<128>& lm, const char* Kh,
+                                                     const char* Vh, float c, int j_first, int step, int count, int lane,
+                                                     LDS_PTR(char) lds) {
+    constexpr int D = 128;
+    using G = Geo<D>;
+    constexpr int KS = D / 16, DB = D / 32;
+    constexpr int NA = 2 * KS;            // K fragments of one tile (each feeds two MFMAs)
+    constexpr int NB = 4 * DB;            // V^T fragments of one tile (each feeds two MFMAs)
+    constexpr int NL = G::kLoadsPerWave;
+    constexpr unsigned VB = kWideBuffers * G::kTile;   // V buffers follow the K buffers
+    if (count <= 0) return;
+    const unsigned lds0 = (unsigned)(size_t)lds;
+    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    f16v A[2][2];       // [half][block]: S^T of the tile one ahead
+    float x[2][32];     // [half]: score*c - M of the current tile
+    u4 pf[2][4];        // [half]: its probabilities as B operands
+    u4 vreg[NL];        // bfloat16 V chunks in flight (BF16 only)
+    float e0[2][16], e1[2][16];
+    float tmax_ahead[2] = {0.f, 0.f};
+    // The Q^T fragments move to accumulation registers for the duration of the range (and back at its end).
+    u4 qa[2][KS];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "=a"(qa[h][ks]) : "0"(st[h].qf[ks]));
+
+    // Tile i of the range lives in K buffer i & 3 and V buffer i & 3.  Fetches beyond the range re-fetch its
+    // last tile into a buffer nobody reads, which keeps the loop free of special cases.
+    auto tile_base = [&](const char* head, int i) {
+        const int ic = i < count ? i : count - 1;
+        return head + (size_t)(j_first + ic * step) * kTileKV * G::kRowBytes;
+    };
+    auto fetch_k = [&](int i, int l) { load_to_lds_16B(tile_base(Kh, i), lm.fill_src[l], lds0 + (i & 3) * G::kTile + lm.fill_dst + l * 4096); };
+    auto fetch_v = [&](int i, int l) { load_to_lds_16B(tile_base(Vh, i), lm.fill_src[l], lds0 + VB + (i & 3) * G::kTile + lm.fill_dst + l * 4096); };
+    auto v_to_regs = [&](int i, int l) { vreg[l] = *reinterpret_cast<const u4*>(tile_base(Vh, i) + lm.fill_src[l]); };
+    // LDS read addresses of this lane: K of the tile one ahead (buffer 1 at the start), V of the current tile
+    unsigned rk[KS], rv[DB][2];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) rk[ks] = lds0 + G::kTile + lm.k_rd[ks];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) { rv[db][0] = lds0 + VB + lm.v_rd[db][0]; rv[db][1] = lds0 + VB + lm.v_rd[db][1]; }
+    auto k_read = [&](int m) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[m / 2] + (m & 1) * 32 * G::kRowBytes); };
+    auto v_read = [&](int idx) -> s8 {
+        const int ks = idx / DB, db = idx % DB;
+        const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][0] + ks * 16 * G::kRowBytes));
+        const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][1] + ks * 16 * G::kRowBytes));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+    auto rescale = [&](int h, float tmax) {
+        const float Mnew = fmaxf(st[h].M, tmax);
+        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st[h].M - Mnew);
+        st[h].M = Mnew;
+        st[h].L *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
+    };
+    // exp unit u (0..16) of half h: the two exponentials of pair u, and the convert + sum of pair u-1
+    auto exp_unit = [&](int h, int u) {
+        if (u < 16) {
+            e0[h][u] = fast_exp2(x[h][2 * u]);
+            e1[h][u] = fast_exp2(x[h][2 * u + 1]);
+        }
+        if (u >= 1 && u <= 16) {
+            const int v = u - 1;
+            const h2 ph = __builtin_convertvector(f2{e0[h][v], e1[h][v]}, h2);
+            st[h].L = __builtin_amdgcn_fdot2(ph, ones, st[h].L, false);
+            pf[h][v / 4][v % 4] = __builtin_bit_cast(unsigned, ph);
+        }
+    };
+    auto shifted_scores = [&](int h) {
+#pragma unroll
+        for (int r = 0; r < 32; ++r) x[h][r] = __builtin_fmaf(A[h][r >> 4][r & 15], c, -st[h].M);
+    };
+
+    // ---------------------------------------------------------------- prologue: K(0..2), V(0..1) on their way, S(0)
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+#pragma unroll
+        for (int l = 0; l < NL; ++l) fetch_k(i, l);
+        if (i < 2) {
+            if constexpr (BF16) {
+#pragma unroll
+                for (int l = 0; l < NL; ++l) v_to_regs(i, l);
+                regs_to_lds_f16<D>(vreg, lm, lane, lds + VB + i * G::kTile);
+            } else {
+#pragma unroll
+                for (int l = 0; l < NL; ++l) fetch_v(i, l);
+            }
+        }
+    }
+    wait_tile_landed();
+    __syncthreads();
+    u4 ak[2];           // the first two K fragments of the tile one ahead, read before the iteration starts
+    {
+        u4 a[NA];
+#pragma unroll
+        for (int m = 0; m < 2; ++m) a[m] = *(LDS_PTR(u4))(size_t)(rk[0] - G::kTile + m * 32 * G::kRowBytes);
+#pragma unroll
+        for (int m = 0; m < NA; ++m) {
+            if (m + 2 < NA) a[m + 2] = *(LDS_PTR(u4))(size_t)(rk[(m + 2) / 2] - G::kTile + ((m + 2) & 1) * 32 * G::kRowBytes);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
+                else mfma_s<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        ak[0] = k_read(0);
+        ak[1] = k_read(1);
+        mfma_settle();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            float mx = fmaxf(A[h][0][0], A[h][0][1]);
+#pragma unroll
+            for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, A[h][r >> 4][r & 15]), A[h][r >> 4][(r & 15) + 1]);
+            const float tmax = pair_max(mx) * c;
+            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + kRescaleSlack)) != 0) rescale(h, tmax);
+            shifted_scores(h);
+        }
+    }
+
+    // ---------------------------------------------------------------- steady state: iteration i
+    // computes S(i+1) from K buffer (i+1)&3 and adds V(i)^T P(i)^T from V buffer i&3; fetches K(i+3) and V(i+2).
+    // Its barrier sits in the middle of the second product: by then everything fetched before this
+    // iteration (K(i+2), V(i+1) among it) has landed, so the first fragments of the next iteration can be read
+    // before this one ends, and the buffers this iteration's fetches overwrite (of K(i-1), V(i-2)) were last
+    // read before the previous barrier.  Returns whether a reference maximum has to be raised before
+    // tile i+1 can be used.
+    auto iteration = [&](int i) -> bool {
+        const unsigned vdst = lds0 + VB + ((i + 2) & 3) * G::kTile + lm.fill_dst;
+        s8 av[NB];
+        // ---- phase A: S(i+1)^T for both halves, exponentials of tile i in between
+        {
+            u4 a[NA];
+            a[0] = ak[0];
+            a[1] = ak[1];
+#pragma unroll
+            for (int m = 0; m < NA; ++m) {
+                if (m + 2 < NA) a[m + 2] = k_read(m + 2);
+                else av[m + 2 - NA] = v_read(m + 2 - NA);      // the first V^T fragments of the second product
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
+                    else mfma_s<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
+                    exp_unit(h, m);
+                    if (h == 0 && (m & 1) == 0) {
+                        const int li = m / 2;        // 8 loads over 16 fragments
+                        if (li < NL) fetch_k(i + 3, li);
+                        else if constexpr (BF16) v_to_regs(i + 2, li - NL);
+                        else fetch_v(i + 2, li - NL);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            exp_unit(0, 16);
+            exp_unit(1, 16);
+        }
+        // K read addresses move on to tile i+2
+        {
+            const int dk = ((i + 2) & 3) ? G::kTile : -3 * G::kTile;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) rk[ks] += dk;
+        }
+        // ---- phase B, first half: row maxima of A and the rescale check
+        float mx[2] = {0.f, 0.f};
+        constexpr int HB = NB / 2;         // fragments before the check
+        constexpr int MS = 1;              // first fragment whose slots may read A (MFMA result latency)
+        constexpr int MPS = (16 + (HB - MS) - 1) / (HB - MS);   // max3 ops per slot and half
+#pragma unroll
+        for (int idx = 0; idx < HB; ++idx) {
+            av[idx + 2] = v_read(idx + 2);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
+                if (idx >= MS) {
+#pragma unroll
+                    for (int q = 0; q < MPS; ++q) {
+                        const int op = (idx - MS) * MPS + q;   // op-th max3 of half h: elements 2*op, 2*op+1
+                        if (op < 16) {
+                            const float u0 = A[h][(2 * op) >> 4][(2 * op) & 15], u1 = A[h][(2 * op) >> 4][((2 * op) & 15) + 1];
+                            mx[h] = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx[h], u0), u1);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        tmax_ahead[0] = pair_max(mx[0]) * c;
+        tmax_ahead[1] = pair_max(mx[1]) * c;
+        const bool need = __builtin_amdgcn_ballot_w64(!(tmax_ahead[0] <= st[0].M + kRescaleSlack) ||
+                                                      !(tmax_ahead[1] <= st[1].M + kRescaleSlack)) != 0;
+        // ---- everything fetched before this iteration has landed; publish it
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        __syncthreads();
+        // ---- phase B, second half, with the shifted scores of tile i+1 in between (and, for
+        //      bfloat16, the conversion of the fetched V chunks)
+        constexpr int FPS = 32 / (NB - HB);                        // fmas per slot and half
+        constexpr int CPS = (NL * 4 + 2 * (NB - HB) - 1) / (2 * (NB - HB));   // bf16 pair conversions per slot
+#pragma unroll
+        for (int idx = HB; idx < NB; ++idx) {
+            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
+            else ak[idx + 2 - NB] = k_read(idx + 2 - NB);       // the first K fragments of the next iteration
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
+#pragma unroll
+                for (int q = 0; q < FPS; ++q) {
+                    const int r = (idx - HB) * FPS + q;
+                    x[h][r] = __builtin_fmaf(A[h][r >> 4][r & 15], c, -st[h].M);
+                }
+                if constexpr (BF16) {
+#pragma unroll
+                    for (int q = 0; q < CPS; ++q) {
+                        const int w = ((idx - HB) * 2 + h) * CPS + q;    // w-th 32-bit word of the fetched chunks
+                        if (w < NL * 4) {
+                            f2 y;
+                            y[0] = __builtin_bit_cast(float, vreg[w / 4][w % 4] << 16);
+                            y[1] = __builtin_bit_cast(float, vreg[w / 4][w % 4] & 0xffff0000u);
+                            vreg[w / 4][w % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(y, h2));
+                            if (w % 4 == 3)
+                                *(LDS_PTR(u4))(size_t)(vdst + (w / 4) * 4096 + lane * 16) = vreg[w / 4];
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // V read addresses move on to tile i+1
+        {
+            const int dv = ((i + 1) & 3) ? G::kTile : -3 * G::kTile;
+#pragma unroll
+            for (int db = 0; db < DB; ++db) { rv[db][0] += dv; rv[db][1] += dv; }
+        }
+        return need;
+    };
+    auto raise_reference = [&]() {
+        mfma_settle();
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            if (__builtin_amdgcn_ballot_w64(!(tmax_ahead[h] <= st[h].M + kRescaleSlack)) != 0) {
+                rescale(h, tmax_ahead[h]);
+                shifted_scores(h);
+            }
+        }
+    };
+    int i = 0;
+    while (i + 1 < count) {
+        bool need = false;
+#pragma unroll 1
+        for (; i + 1 < count; ++i) {
+            need = iteration(i);
+            if (need) { ++i; break; }
+        }
+        if (need) raise_reference();
+    }
+
+    // ---------------------------------------------------------------- last tile: probabilities, then O^T += V^T P^T
+#pragma unroll
+    for (int u = 0; u <= 16; ++u) { exp_unit(0, u); exp_unit(1, u); }
+    {
+        s8 av[NB];
+        av[0] = v_read(0);
+        av[1] = v_read(1);
+#pragma unroll
+        for (int idx = 0; idx < NB; ++idx) {
+            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    mfma_settle();     // the accumulators are complete before the caller's vector code reads them
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "=v"(st[h].qf[ks]) : "0"(qa[h][ks]));
+    wait_tile_landed();   // also the fetches past the end of the range
+    __syncthreads();      // all reads of the last tile are done before anything refills the buffers
+}
+
+// One query tile (Alg. 1 body): rows [t*128*NH, (t+1)*128*NH) of head `hh`, K/V tiles j0, j0+step, ... (nkv of
+// them).  A wavefront owns NH halves of 32 query rows each (NH = 2: the wide variant).
+template <int D, bool BF16, bool CAUSAL, int NH>
 __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>& lm, int hh, int t, int j0, int step,
                                                int nkv, int wave, int lane, LDS_PTR(char) lds) {
     using G = Geo<D>;
     constexpr int KS = D / 16;    // MFMA steps along d for S^T
     constexpr int DB = D / 32;    // 32-row blocks of O^T
+    constexpr int TQ = kTileQ * NH;
     const int g = lane >> 5, ln = lane & 31;
     const int N = p.N;
     const size_t head_off = (size_t)hh * N * G::kRowBytes;
@@ -708,64 +1027,74 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
     const char* Kh = static_cast<const char*>(p.K) + head_off;
     const char* Vh = static_cast<const char*>(p.V) + head_off;
 
-    const int qw0 = t * kTileQ + wave * 32;   // first query row of this wavefront
-    const int qrow = qw0 + ln;                // this lane's query row (column of S^T)
-    const bool wave_has_rows = qw0 < N;
+    const int qw0 = t * TQ + wave * 32 * NH;  // first query row of this wavefront
+    const int qrow = qw0 + ln;                // this lane's query row in half 0 (column of S^T)
 
-    TileState<D> st;
-    {   // rows beyond N repeat row N-1 (computed, never stored)
-        const int qr = qrow < N ? qrow : N - 1;
+    TileState<D> st[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {   // rows beyond N repeat row N-1 (computed, never stored)
+        const int qr = qrow + 32 * h < N ? qrow + 32 * h : N - 1;
         const char* qp = Qh + (size_t)qr * G::kRowBytes + g * 16;
         const unsigned flip = p.negate_q ? 0x80008000u : 0u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
             v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
-            st.qf[ks] = v;
+            st[h].qf[ks] = v;
         }
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st[h].o[db][r] = 0.f;
+        st[h].M = -INFINITY;
+        st[h].L = 0.f;
     }
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
-    st.M = -INFINITY;
-    st.L = 0.f;
     const float c = p.c;
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
     // the tiles that reach past the first row of this query tile.  They sit at one end of the scan,
     // so the scan is a pipelined run of plain tiles and a run of masked tiles, in scan order.
     const int kv_tiles = (N + kTileKV - 1) / kTileKV;
-    const int jm = CAUSAL ? (t * kTileQ) / kTileKV : ((N % kTileKV) ? kv_tiles - 1 : kv_tiles);
+    const int jm = CAUSAL ? (t * TQ) / kTileKV : ((N % kTileKV) ? kv_tiles - 1 : kv_tiles);
     const int n_masked = nkv > jm ? nkv - jm : 0;
     const int n_plain = nkv - n_masked;
+    auto plain = [&](int j_first) {
+        if constexpr (NH == 1) pipelined_range<D, BF16>(st[0], lm, Kh, Vh, c, j_first, step, n_plain, lane, lds);
+        else pipelined_range_wide<BF16>(st, lm, Kh, Vh, c, j_first, step, n_plain, lane, lds);
+    };
+    auto masked = [&](int j_first) {
+        general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, lane, lds);
+    };
     if (step > 0) {
-        pipelined_range<D, BF16>(st, lm, Kh, Vh, c, j0, step, n_plain, lane, lds);
-        general_range<D, BF16, CAUSAL, true>(st, lm, Kh, Vh, N, c, j0 + n_plain * step, step, n_masked, qw0, qrow, wave_has_rows, lane, lds);
+        plain(j0);
+        masked(j0 + n_plain * step);
     } else {
-        general_range<D, BF16, CAUSAL, true>(st, lm, Kh, Vh, N, c, j0, step, n_masked, qw0, qrow, wave_has_rows, lane, lds);
-        pipelined_range<D, BF16>(st, lm, Kh, Vh, c, j0 + n_masked * step, step, n_plain, lane, lds);
+        masked(j0);
+        plain(j0 + n_masked * step);
     }
 
     // ---- epilogue: O_i = acc / l  (the division Alg. 1 leaves implicit; Eq. 1 fixes it)
-    const float inv = 1.0f / pair_sum(st.L);
-    if (qrow < N) {
-        const size_t orow = ((size_t)hh * N + qrow) * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+    for (int h = 0; h < NH; ++h) {
+        const float inv = 1.0f / pair_sum(st[h].L);
+        if (qrow + 32 * h < N) {
+            const size_t orow = ((size_t)hh * N + qrow + 32 * h) * D;
 #pragma unroll
-            for (int rq = 0; rq < 4; ++rq) {
-                const f16v& o = st.o[db];
-                f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
-                const size_t col = 32 * db + 8 * rq + 4 * g;
-                if (p.o_dtype == SAWATTN_F32) {
-                    *reinterpret_cast<f4*>(static_cast<float*>(p.O) + orow + col) = v;
-                } else if (p.o_dtype == SAWATTN_F16) {
-                    *reinterpret_cast<h4*>(static_cast<_Float16*>(p.O) + orow + col) = __builtin_convertvector(v, h4);
-                } else {
-                    *reinterpret_cast<b4*>(static_cast<__bf16*>(p.O) + orow + col) = __builtin_convertvector(v, b4);
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    const f16v& o = st[h].o[db];
+                    f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
+                    const size_t col = 32 * db + 8 * rq + 4 * g;
+                    if (p.o_dtype == SAWATTN_F32) {
+                        *reinterpret_cast<f4*>(static_cast<float*>(p.O) + orow + col) = v;
+                    } else if (p.o_dtype == SAWATTN_F16) {
+                        *reinterpret_cast<h4*>(static_cast<_Float16*>(p.O) + orow + col) = __builtin_convertvector(v, h4);
+                    } else {
+                        *reinterpret_cast<b4*>(static_cast<__bf16*>(p.O) + orow + col) = __builtin_convertvector(v, b4);
+                    }
                 }
-            }
+        }
     }
 }
 
@@ -801,8 +1130,8 @@ __device__ __forceinline__ void domain_sync(int domain, int slots) {
     __syncthreads();
 }
 
-template <int D, bool BF16, bool CAUSAL>
-__global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void attn_fwd_kernel(Params p) {
+template <int D, bool BF16, bool CAUSAL, int NH>
+__global__ __launch_bounds__(kThreads, NH == 2 ? 1 : (D == 64 ? 3 : 2)) void attn_fwd_kernel(Params p) {
     extern __shared__ __align__(16) char smem[];
     const Schedule& s = p.sched;
     const int lane0 = threadIdx.x & 63;
@@ -823,7 +1152,7 @@ __global__ __launch_bounds__(kThreads, D == 64 ? 3 : 2) void attn_fwd_kernel(Par
             int lane = lane0;
             asm volatile("" : "+v"(lane));
             const LaneMap<D> lm(wave, lane);
-            process_q_tile<D, BF16, CAUSAL>(p, lm, w.head, w.tile, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
+            process_q_tile<D, BF16, CAUSAL, NH>(p, lm, w.head, w.tile, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
             ++local;
         }
         // Every workgroup of the domain comes here once per head, also those that sat rounds out.
@@ -927,11 +1256,11 @@ int check_shape(int B, int H, int N, int d) {
 }
 
 void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
-    out->tile_q = kTileQ;
+    out->tile_q = s.tile_q;
     out->tile_kv = kTileKV;
     out->block_threads = kThreads;
     out->grid = s.grid;
-    out->lds_bytes = d == 128 ? Geo<128>::kLdsBytes : Geo<64>::kLdsBytes;
+    out->lds_bytes = s.tile_q > kTileQ ? kWideLdsBytes : (d == 128 ? Geo<128>::kLdsBytes : Geo<64>::kLdsBytes);
     out->domains = kDomains;
     out->slots = s.slots;
     out->parts_per_head = s.parts;
@@ -939,20 +1268,21 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
     out->max_local_tiles = s.local_iters;
 }
 
-template <int D, bool BF16, bool CAUSAL>
+template <int D, bool BF16, bool CAUSAL, int NH>
 int launch(const Params& p, int grid, hipStream_t stream) {
-    auto kern = attn_fwd_kernel<D, BF16, CAUSAL>;
+    auto kern = attn_fwd_kernel<D, BF16, CAUSAL, NH>;
+    constexpr int lds_bytes = NH == 2 ? kWideLdsBytes : Geo<D>::kLdsBytes;
     static thread_local bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                Geo<D>::kLdsBytes) != hipSuccess) {
+                                lds_bytes) != hipSuccess) {
             (void)hipGetLastError();
             return fail(SAWATTN_ERR_RUNTIME, "hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
         }
         configured = true;
     }
     if (p.sched.sync_heads) hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), Geo<D>::kLdsBytes, stream, p);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds_bytes, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         char msg[200];
@@ -964,22 +1294,29 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
 int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant* v, Schedule* out) {
-    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = resident_slots(d), tiles_per_wg = 2;
+    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, tile_q = kTileQ;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
         if (v->decode != SAWATTN_DECODE_DOMAIN && v->decode != SAWATTN_DECODE_LINEAR)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.decode must be SAWATTN_DECODE_DOMAIN or SAWATTN_DECODE_LINEAR");
-        if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d))
-            return fail(SAWATTN_ERR_INVALID_ARG, "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64)");
+        if (v->rows_per_wavefront != 0 && v->rows_per_wavefront != 32 && v->rows_per_wavefront != 64)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.rows_per_wavefront must be 0 (default), 32 or 64");
+        if (v->rows_per_wavefront == 64 && d != 128)
+            return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
+        if (v->rows_per_wavefront == 64) tile_q = 2 * kTileQ;
+        if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, tile_q))
+            return fail(SAWATTN_ERR_INVALID_ARG,
+                        "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per wavefront)");
         if (v->tiles_per_workgroup < 0 || v->tiles_per_workgroup > 2)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.tiles_per_workgroup must be 0 (default), 1 or 2");
         launch = v->launch == SAWATTN_LAUNCH_GRID ? kLaunchGrid : kLaunchPersistent;
         decode = v->decode == SAWATTN_DECODE_LINEAR ? kDecodeLinear : kDecodeDomain;
-        if (v->slots_per_domain) max_slots = v->slots_per_domain;
+        max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
     }
-    *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg);
+    if (max_slots == 0) max_slots = resident_slots(d, tile_q);
+    *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q);
     return SAWATTN_OK;
 }
 
@@ -1026,12 +1363,16 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     const int grid = sched.grid;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool bf = in_dtype == SAWATTN_BF16, ca = causal != 0;
-    if (d == 128) {
-        if (bf) return ca ? launch<128, true, true>(p, grid, stream) : launch<128, true, false>(p, grid, stream);
-        return ca ? launch<128, false, true>(p, grid, stream) : launch<128, false, false>(p, grid, stream);
+    if (sched.tile_q > kTileQ) {
+        if (bf) return ca ? launch<128, true, true, 2>(p, grid, stream) : launch<128, true, false, 2>(p, grid, stream);
+        return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
-    if (bf) return ca ? launch<64, true, true>(p, grid, stream) : launch<64, true, false>(p, grid, stream);
-    return ca ? launch<64, false, true>(p, grid, stream) : launch<64, false, false>(p, grid, stream);
+    if (d == 128) {
+        if (bf) return ca ? launch<128, true, true, 1>(p, grid, stream) : launch<128, true, false, 1>(p, grid, stream);
+        return ca ? launch<128, false, true, 1>(p, grid, stream) : launch<128, false, false, 1>(p, grid, stream);
+    }
+    if (bf) return ca ? launch<64, true, true, 1>(p, grid, stream) : launch<64, true, false, 1>(p, grid, stream);
+    return ca ? launch<64, false, true, 1>(p, grid, stream) : launch<64, false, false, 1>(p, grid, stream);
 }
 
 }  // namespace sawattn

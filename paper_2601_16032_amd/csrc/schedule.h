@@ -32,7 +32,7 @@
 
 namespace sawattn {
 
-constexpr int kTileQ = 128;      // query rows per workgroup tile
+constexpr int kTileQ = 128;      // query rows per workgroup tile (twice that in the wide variant)
 constexpr int kTileKV = 64;      // key/value rows per streamed tile
 constexpr int kThreads = 256;    // 4 wavefronts, 32 query rows each
 constexpr int kDomains = 8;      // XCDs
@@ -40,7 +40,8 @@ constexpr int kMaxSlots = 96;    // largest number of workgroups per domain for 
 
 // Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
 // dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for two.
-SAW_HD int resident_slots(int d) { return d == 64 ? 96 : 64; }
+// The wide variant (256-row tiles, up to 512 registers per wavefront) runs one workgroup per CU.
+SAW_HD int resident_slots(int d, int tile_q = kTileQ) { return tile_q > kTileQ ? 32 : (d == 64 ? 96 : 64); }
 
 // Besides that default, the launch variants the paper describes are kept selectable so that they
 // can be measured against it: the literal global stride of Alg. 2 (workgroup k takes the linear
@@ -53,7 +54,8 @@ enum { kDecodeDomain = 0, kDecodeLinear = 1 };
 
 struct Schedule {
     int heads;              // B*H
-    int q_tiles;            // ceil(N / kTileQ)
+    int tile_q;             // query rows per workgroup tile: kTileQ, or 2*kTileQ in the wide variant
+    int q_tiles;            // ceil(N / tile_q)
     int kv_tiles;           // ceil(N / kTileKV)
     int launch;             // kLaunchPersistent | kLaunchGrid
     int decode;             // kDecodeDomain | kDecodeLinear
@@ -79,10 +81,12 @@ SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } retu
 SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // max_slots in 1..resident_slots(d), tiles_per_wg in {1, 2}; the caller has validated them.
-SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int decode, int max_slots, int tiles_per_wg) {
+SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int decode, int max_slots, int tiles_per_wg,
+                              int tile_q = kTileQ) {
     Schedule s;
     s.heads = heads;
-    s.q_tiles = (N + kTileQ - 1) / kTileQ;
+    s.tile_q = tile_q;
+    s.q_tiles = (N + tile_q - 1) / tile_q;
     s.kv_tiles = (N + kTileKV - 1) / kTileKV;
     s.launch = launch;
     s.decode = decode;
@@ -163,7 +167,7 @@ SAW_HD Work decode_work(const Schedule& s, int wg, int it, bool causal, bool saw
 // K/V tiles visible to query tile t.
 SAW_HD int visible_kv_tiles(const Schedule& s, int t, int N, bool causal) {
     if (!causal) return s.kv_tiles;
-    long long last_row = (long long)(t + 1) * kTileQ;
+    long long last_row = (long long)(t + 1) * s.tile_q;
     if (last_row > N) last_row = N;
     return (int)((last_row + kTileKV - 1) / kTileKV);
 }
