@@ -168,6 +168,12 @@ __device__ __forceinline__ void load_to_lds_16B(const char* base, unsigned voff,
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
+// The same with the LDS address given as a scalar base plus a compile-time offset (one scalar add into M0).
+template <int LDS_IMM>
+__device__ __forceinline__ void load_to_lds_16B_at(const char* base, unsigned voff, unsigned lds_base) {
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(voff), "s"(base), "n"(LDS_IMM) : "memory", "m0", "scc");
+}
 __device__ __forceinline__ void wait_tile_landed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Per-lane byte offsets (relative to the head's base) of this lane's chunks of tile j.  A ragged
@@ -739,6 +745,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     constexpr int NB = 4 * DB;            // V^T fragments of one tile (each feeds two MFMAs)
     constexpr int NL = G::kLoadsPerWave;
     constexpr unsigned VB = kWideBuffers * G::kTile;   // V buffers follow the K buffers
+    constexpr int RA = 3;                 // LDS fragments are read this many fragments ahead of their MFMAs
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
     const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
@@ -788,17 +795,21 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
     };
     // exp unit u (0..16) of half h: the two exponentials of pair u, and the convert + sum of pair u-1
+    // (with one wavefront per SIMD nothing hides the latency between dependent vector instructions, so the
+    // convert comes first and the sum that needs its result last)
     auto exp_unit = [&](int h, int u) {
+        h2 ph;
+        if (u >= 1 && u <= 16) {
+            ph = __builtin_convertvector(f2{e0[h][u - 1], e1[h][u - 1]}, h2);
+            pf[h][(u - 1) / 4][(u - 1) % 4] = __builtin_bit_cast(unsigned, ph);
+            __builtin_amdgcn_sched_barrier(0);
+        }
         if (u < 16) {
             e0[h][u] = fast_exp2(x[h][2 * u]);
             e1[h][u] = fast_exp2(x[h][2 * u + 1]);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (u >= 1 && u <= 16) {
-            const int v = u - 1;
-            const h2 ph = __builtin_convertvector(f2{e0[h][v], e1[h][v]}, h2);
-            st[h].L = __builtin_amdgcn_fdot2(ph, ones, st[h].L, false);
-            pf[h][v / 4][v % 4] = __builtin_bit_cast(unsigned, ph);
-        }
+        if (u >= 1 && u <= 16) st[h].L = __builtin_amdgcn_fdot2(ph, ones, st[h].L, false);
     };
     auto shifted_scores = [&](int h) {
 #pragma unroll
@@ -823,14 +834,14 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     }
     wait_tile_landed();
     __syncthreads();
-    u4 ak[2];           // the first two K fragments of the tile one ahead, read before the iteration starts
+    u4 ak[RA];          // the first K fragments of the tile one ahead, read before the iteration starts
     {
         u4 a[NA];
 #pragma unroll
-        for (int m = 0; m < 2; ++m) a[m] = *(LDS_PTR(u4))(size_t)(rk[0] - G::kTile + m * 32 * G::kRowBytes);
+        for (int m = 0; m < RA; ++m) a[m] = *(LDS_PTR(u4))(size_t)(rk[m / 2] - G::kTile + (m & 1) * 32 * G::kRowBytes);
 #pragma unroll
         for (int m = 0; m < NA; ++m) {
-            if (m + 2 < NA) a[m + 2] = *(LDS_PTR(u4))(size_t)(rk[(m + 2) / 2] - G::kTile + ((m + 2) & 1) * 32 * G::kRowBytes);
+            if (m + RA < NA) a[m + RA] = *(LDS_PTR(u4))(size_t)(rk[(m + RA) / 2] - G::kTile + ((m + RA) & 1) * 32 * G::kRowBytes);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
@@ -838,8 +849,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        ak[0] = k_read(0);
-        ak[1] = k_read(1);
+#pragma unroll
+        for (int m = 0; m < RA; ++m) ak[m] = k_read(m);
         mfma_settle();
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -861,26 +872,43 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     // tile i+1 can be used.
     auto iteration = [&](int i) -> bool {
         const unsigned vdst = lds0 + VB + ((i + 2) & 3) * G::kTile + lm.fill_dst;
+        // this iteration's fetches: K(i+3) and V(i+2), source tile bases and LDS destinations of this wavefront
+        const char* kbase = tile_base(Kh, i + 3);
+        const char* vbase = tile_base(Vh, i + 2);
+        const unsigned kdst_s = __builtin_amdgcn_readfirstlane(lds0 + ((i + 3) & 3) * G::kTile + lm.fill_dst);
+        const unsigned vdst_s = __builtin_amdgcn_readfirstlane(vdst);
         s8 av[NB];
         // ---- phase A: S(i+1)^T for both halves, exponentials of tile i in between
         {
             u4 a[NA];
-            a[0] = ak[0];
-            a[1] = ak[1];
+#pragma unroll
+            for (int m = 0; m < RA; ++m) a[m] = ak[m];
+            auto constexpr_fetch = [&](int li) {
+                if (li < NL) {
+                    if (li == 0) load_to_lds_16B_at<0>(kbase, lm.fill_src[0], kdst_s);
+                    if (li == 1) load_to_lds_16B_at<4096>(kbase, lm.fill_src[1], kdst_s);
+                    if (li == 2) load_to_lds_16B_at<8192>(kbase, lm.fill_src[2], kdst_s);
+                    if (li == 3) load_to_lds_16B_at<12288>(kbase, lm.fill_src[3], kdst_s);
+                } else if constexpr (BF16) {
+                    vreg[li - NL] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[li - NL]);
+                } else {
+                    if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
+                    if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
+                    if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
+                    if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
+                }
+            };
 #pragma unroll
             for (int m = 0; m < NA; ++m) {
-                if (m + 2 < NA) a[m + 2] = k_read(m + 2);
-                else av[m + 2 - NA] = v_read(m + 2 - NA);      // the first V^T fragments of the second product
+                if (m + RA < NA) a[m + RA] = k_read(m + RA);
+                else av[m + RA - NA] = v_read(m + RA - NA);    // the first V^T fragments of the second product
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
                     else mfma_s<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
                     exp_unit(h, m);
                     if (h == 0 && (m & 1) == 0) {
-                        const int li = m / 2;        // 8 loads over 16 fragments
-                        if (li < NL) fetch_k(i + 3, li);
-                        else if constexpr (BF16) v_to_regs(i + 2, li - NL);
-                        else fetch_v(i + 2, li - NL);
+                        constexpr_fetch(m / 2);      // 8 loads over 16 fragments
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -899,19 +927,22 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         constexpr int HB = NB / 2;         // fragments before the check
         constexpr int MS = 1;              // first fragment whose slots may read A (MFMA result latency)
         constexpr int MPS = (16 + (HB - MS) - 1) / (HB - MS);   // max3 ops per slot and half
+        // (the two halves' maxima are separate dependency chains; their steps alternate)
 #pragma unroll
         for (int idx = 0; idx < HB; ++idx) {
-            av[idx + 2] = v_read(idx + 2);
+            av[idx + RA] = v_read(idx + RA);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
                 if (idx >= MS) {
 #pragma unroll
                     for (int q = 0; q < MPS; ++q) {
-                        const int op = (idx - MS) * MPS + q;   // op-th max3 of half h: elements 2*op, 2*op+1
+                        const int step2 = ((idx - MS) * 2 + h) * MPS + q;   // step of the alternating sequence
+                        const int hh = step2 & 1, op = step2 >> 1;          // op-th max3 of half hh: elements 2*op, 2*op+1
                         if (op < 16) {
-                            const float u0 = A[h][(2 * op) >> 4][(2 * op) & 15], u1 = A[h][(2 * op) >> 4][((2 * op) & 15) + 1];
-                            mx[h] = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx[h], u0), u1);
+                            const float u0 = A[hh][(2 * op) >> 4][(2 * op) & 15], u1 = A[hh][(2 * op) >> 4][((2 * op) & 15) + 1];
+                            mx[hh] = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx[hh], u0), u1);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     }
                 }
@@ -931,8 +962,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         constexpr int CPS = (NL * 4 + 2 * (NB - HB) - 1) / (2 * (NB - HB));   // bf16 pair conversions per slot
 #pragma unroll
         for (int idx = HB; idx < NB; ++idx) {
-            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
-            else ak[idx + 2 - NB] = k_read(idx + 2 - NB);       // the first K fragments of the next iteration
+            if (idx + RA < NB) av[idx + RA] = v_read(idx + RA);
+            else ak[idx + RA - NB] = k_read(idx + RA - NB);     // the first K fragments of the next iteration
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
@@ -992,11 +1023,11 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     for (int u = 0; u <= 16; ++u) { exp_unit(0, u); exp_unit(1, u); }
     {
         s8 av[NB];
-        av[0] = v_read(0);
-        av[1] = v_read(1);
+#pragma unroll
+        for (int idx = 0; idx < RA; ++idx) av[idx] = v_read(idx);
 #pragma unroll
         for (int idx = 0; idx < NB; ++idx) {
-            if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
+            if (idx + RA < NB) av[idx + RA] = v_read(idx + RA);
 #pragma unroll
             for (int h = 0; h < 2; ++h) mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
             __builtin_amdgcn_sched_barrier(0);
