@@ -98,14 +98,16 @@ typedef struct sawattn_variant {
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
                                 0 = default (2).  Ignored by the persistent launch. */
     int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
-                                64 (d = 128 only): 256 rows, one workgroup per CU, every K/V fragment read
-                                from LDS feeds two MFMAs; 0 = default (32). */
+                                64 (d = 128 only): 256 rows, one workgroup per CU (at most 32 per XCD), every
+                                K/V fragment read from LDS feeds two MFMAs; 0 = default: 64 when d = 128 and
+                                every workgroup of an XCD gets at least two 256-row tiles of a head
+                                (ceil(ceil(N/256) / parts_per_head) >= 64) and slots_per_domain <= 32, else 32. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round
  * over the current head (the default); persistent + linear decode: parity of the workgroup's own
  * iteration count (Alg. 4 as printed); grid launch: parity of the tile's position in its workgroup.
- * A NULL variant pointer selects { PERSISTENT, DOMAIN, 0, 0 }, which is what attn_fwd runs.
+ * A NULL variant pointer selects { PERSISTENT, DOMAIN, 0, 0, 0 }, which is what attn_fwd runs.
  */
 
 /*

@@ -37,9 +37,22 @@ from math import gcd
 T_Q, T_KV, DOMAINS = 128, 64, 8
 
 
-def resident_slots(d: int) -> int:
-    """Workgroups of one domain that run at the same time: 32 CUs x 3 per CU at d = 64, x 2 at d = 128."""
+def resident_slots(d: int, rows_per_wavefront: int = 32) -> int:
+    """Workgroups of one domain that run at the same time: 32 CUs x 3 per CU at d = 64, x 2 at d = 128,
+    x 1 when a wavefront holds 64 query rows."""
+    if rows_per_wavefront == 64:
+        return 32
     return 96 if d == 64 else 64
+
+
+def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0) -> int:
+    """The library's choice when the caller leaves it open: 64 rows per wavefront (256-row tiles) at d = 128
+    if every workgroup of a domain then still gets two tiles of a head, and the caller did not ask for
+    more workgroups per domain than fit that way."""
+    if d != 128 or slots_per_domain > 32:
+        return 32
+    parts = DOMAINS // gcd(heads, DOMAINS)
+    return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= 64 else 32
 
 
 def ceil_div(a: int, b: int) -> int:
@@ -47,10 +60,12 @@ def ceil_div(a: int, b: int) -> int:
 
 
 def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",
-                    slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128):
-    slots_per_domain = slots_per_domain or resident_slots(d)
+                    slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128, rows_per_wavefront: int = 0):
     heads = B * H
-    q_tiles = ceil_div(N, T_Q)
+    rows = rows_per_wavefront or rows_per_wavefront_for(heads, N, d, slots_per_domain)
+    tile_q = T_Q * rows // 32
+    slots_per_domain = slots_per_domain or resident_slots(d, rows)
+    q_tiles = ceil_div(N, tile_q)
     total = heads * q_tiles
     if decode == "linear":
         if launch == "persistent":
@@ -59,7 +74,8 @@ def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: 
         else:
             slots = ceil_div(ceil_div(total, tiles_per_workgroup), DOMAINS)
             local = tiles_per_workgroup
-        return {"grid": DOMAINS * slots, "slots": slots, "parts": 1, "q_tiles": q_tiles, "max_local": local}
+        return {"grid": DOMAINS * slots, "slots": slots, "parts": 1, "q_tiles": q_tiles, "max_local": local,
+                "tile_q": tile_q}
     parts = DOMAINS // gcd(heads, DOMAINS)
     largest_part = ceil_div(q_tiles, parts)
     chunks_per_domain = heads * parts // DOMAINS
@@ -68,32 +84,34 @@ def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: 
         rounds = ceil_div(largest_part, slots)
         return {"grid": DOMAINS * slots, "slots": slots, "parts": parts, "q_tiles": q_tiles,
                 "rounds_per_chunk": rounds, "chunks_per_domain": chunks_per_domain,
-                "max_local": chunks_per_domain * rounds}
+                "max_local": chunks_per_domain * rounds, "tile_q": tile_q}
     units = ceil_div(largest_part, tiles_per_workgroup)
     slots = chunks_per_domain * units
     return {"grid": DOMAINS * slots, "slots": slots, "parts": parts, "q_tiles": q_tiles,
-            "units_per_chunk": units, "chunks_per_domain": chunks_per_domain, "max_local": tiles_per_workgroup}
+            "units_per_chunk": units, "chunks_per_domain": chunks_per_domain, "max_local": tiles_per_workgroup,
+            "tile_q": tile_q}
 
 
-def visible_kv(t: int, N: int, causal: bool) -> int:
-    """Number of K/V tiles query tile t has to visit."""
+def visible_kv(t: int, N: int, causal: bool, tile_q: int = T_Q) -> int:
+    """Number of K/V tiles query tile t (of tile_q rows) has to visit."""
     if not causal:
         return ceil_div(N, T_KV)
-    last_row = min((t + 1) * T_Q, N)          # rows of the tile are t*T_Q .. last_row-1
+    last_row = min((t + 1) * tile_q, N)       # rows of the tile are t*tile_q .. last_row-1
     return ceil_div(last_row, T_KV)
 
 
-def record(head: int, t: int, N: int, causal: bool, backward: bool):
-    n_kv = visible_kv(t, N, causal)
+def record(head: int, t: int, N: int, causal: bool, backward: bool, tile_q: int = T_Q):
+    n_kv = visible_kv(t, N, causal, tile_q)
     return (head, t, n_kv - 1, 0) if backward else (head, t, 0, n_kv - 1)
 
 
 def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str = "persistent",
-             decode: str = "domain", slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128):
+             decode: str = "domain", slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128,
+             rows_per_wavefront: int = 0):
     """Return {workgroup: [(head, query tile, first K/V tile, last K/V tile), ...]} in the order
     each workgroup processes its tiles."""
-    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d)
-    heads, parts, slots, grid = B * H, geo["parts"], geo["slots"], geo["grid"]
+    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d, rows_per_wavefront)
+    heads, parts, slots, grid, tq = B * H, geo["parts"], geo["slots"], geo["grid"], geo["tile_q"]
     saw = scan_order == "sawtooth"
     out = {}
     if decode == "linear":
@@ -101,7 +119,7 @@ def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str 
         for wg in range(grid):
             mine = work[wg::grid] if launch == "persistent" else \
                 work[wg * tiles_per_workgroup:(wg + 1) * tiles_per_workgroup]
-            out[wg] = [record(head, t, N, causal, saw and i % 2 == 1) for i, (head, t) in enumerate(mine)]
+            out[wg] = [record(head, t, N, causal, saw and i % 2 == 1, tq) for i, (head, t) in enumerate(mine)]
         return out
     for domain in range(DOMAINS):
         my_chunks = [c for c in range(heads * parts) if c % DOMAINS == domain]
@@ -117,7 +135,7 @@ def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str 
             for head, tiles in chunk_tiles:
                 for unit in range(geo["units_per_chunk"]):
                     mine = tiles[unit * tiles_per_workgroup:(unit + 1) * tiles_per_workgroup]
-                    out[m * DOMAINS + domain] = [record(head, t, N, causal, saw and i % 2 == 1)
+                    out[m * DOMAINS + domain] = [record(head, t, N, causal, saw and i % 2 == 1, tq)
                                                  for i, t in enumerate(mine)]
                     m += 1
             continue
@@ -129,6 +147,6 @@ def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str 
                     hand_out = list(range(slots)) if nth_round % 2 == 0 else list(range(slots - 1, -1, -1))
                     pos = r * slots + hand_out.index(slot)
                     if pos < len(tiles):
-                        recs.append(record(head, tiles[pos], N, causal, saw and r % 2 == 1))
+                        recs.append(record(head, tiles[pos], N, causal, saw and r % 2 == 1, tq))
             out[slot * DOMAINS + domain] = recs
     return out

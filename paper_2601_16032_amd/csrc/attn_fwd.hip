@@ -1325,7 +1325,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
 int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant* v, Schedule* out) {
-    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, tile_q = kTileQ;
+    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
@@ -1335,8 +1335,9 @@ int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant*
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.rows_per_wavefront must be 0 (default), 32 or 64");
         if (v->rows_per_wavefront == 64 && d != 128)
             return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
-        if (v->rows_per_wavefront == 64) tile_q = 2 * kTileQ;
-        if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, tile_q))
+        rows = v->rows_per_wavefront;
+        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d);
+        if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : kTileQ))
             return fail(SAWATTN_ERR_INVALID_ARG,
                         "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per wavefront)");
         if (v->tiles_per_workgroup < 0 || v->tiles_per_workgroup > 2)
@@ -1346,6 +1347,8 @@ int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant*
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
     }
+    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d);
+    const int tile_q = rows == 64 ? 2 * kTileQ : kTileQ;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q);
     return SAWATTN_OK;

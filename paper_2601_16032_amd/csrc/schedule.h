@@ -36,10 +36,23 @@ constexpr int kTileQ = 128;      // query rows per workgroup tile (twice that in
 constexpr int kTileKV = 64;      // key/value rows per streamed tile
 constexpr int kThreads = 256;    // 4 wavefronts, 32 query rows each
 constexpr int kDomains = 8;      // XCDs
+SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
+SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
+
 constexpr int kMaxSlots = 96;    // largest number of workgroups per domain for any head dimension
 
 // Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
 // dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for two.
+// Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
+// workgroup tiles) for head dimension 128 once every resident workgroup of a domain gets at least two
+// tiles of a head, i.e. where the steady state dominates; 32 rows otherwise.
+SAW_HD int default_rows_per_wavefront(int heads, int N, int d) {
+    if (d != 128) return 32;
+    const int parts = kDomains / gcd_i(heads, kDomains);
+    const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
+    return (wide_tiles + parts - 1) / parts >= 64 ? 64 : 32;
+}
+
 // The wide variant (256-row tiles, up to 512 registers per wavefront) runs one workgroup per CU.
 SAW_HD int resident_slots(int d, int tile_q = kTileQ) { return tile_q > kTileQ ? 32 : (d == 64 ? 96 : 64); }
 
@@ -77,8 +90,6 @@ struct Work {
     bool sync_after; // persistent domain decode: last round of a head that is not the domain's last
 };
 
-SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
-SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // max_slots in 1..resident_slots(d), tiles_per_wg in {1, 2}; the caller has validated them.
 SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int decode, int max_slots, int tiles_per_wg,

@@ -301,3 +301,57 @@ def test_variants_at_full_size_agree_with_default(sa):
         assert torch.equal(O, base), kw
         O = sa.attn_fwd_variant(Q, K, V, scale=w.scale, causal=False, scan_order="sawtooth", variant=var)
         print(kw, assert_close(O.double().cpu().numpy(), base.double().cpu().numpy(), f"variant {kw}"))
+
+
+# ------------------------------------------------------------------ 64 query rows per wavefront (d = 128)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_wide_rows_variant_small_shapes(sa, oracle, dtype, causal):
+    """256-row workgroup tiles, every length class: shorter than a tile, ragged, one and several tiles,
+    both scan orders, also under the direct launch (second tile backward) and with few slots (many rounds)."""
+    from oracle import schedule_oracle as so
+    for k, N in enumerate([1, 63, 64, 65, 200, 256, 257, 511, 512, 777, 1000, 2048 + 33]):
+        B, H = (1, 2) if k % 2 == 0 else (2, 3)
+        Q, K, V = workloads.make_random(B, H, N, 128, dtype, seed=2000 + N)
+        scale = 1.0 / math.sqrt(128)
+        want = oracle.attention(Q, K, V, scale, causal=causal)
+        for kw in (dict(), dict(launch="grid"), dict(slots_per_domain=1)):
+            var = sa.variant(rows_per_wavefront=64, **kw)
+            for order in ORDERS:
+                O, trace, count = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal,
+                                                      scan_order=order, o_dtype=torch.float32, variant=var, trace=True)
+                torch.cuda.synchronize()
+                assert_close(O.double().cpu().numpy(), want, f"wide N={N} {dtype} causal={causal} {kw} {order}")
+                sched = so.schedule(B, H, N, causal, order, d=128, rows_per_wavefront=64, **kw)
+                trace, count = trace.cpu(), count.cpu()
+                for wg, recs in sched.items():
+                    assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == recs, f"workgroup {wg}"
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal):
+    """A sequence long enough that the library picks 64 rows per wavefront by itself (two rounds of 32 slots per
+    head), with score levels that jump from tile to tile so that the reference maximum is raised again and
+    again in both scan directions; checked on sampled rows, and against the explicit 32-row variant."""
+    H, N, d = 8, 256 * 64 + 100, 128
+    assert sa.attn_fwd_launch_info(1, H, N, d, causal)["tile_q"] == 256
+    g = torch.Generator("cpu").manual_seed(99)
+    level = 60.0 * torch.rand(H, (N + 63) // 64, generator=g)
+    level[:, 7] = 75.0
+    level[:, -11] = 74.0
+    K = torch.randn(1, H, N, d, generator=g)
+    K[0, :, :, 0] = level.repeat_interleave(64, dim=1)[:, :N]
+    Q = 0.3 * torch.randn(1, H, N, d, generator=g)
+    Q[0, :, :, 0] = 4.0
+    V = torch.randn(1, H, N, d, generator=g)
+    Q, K, V = Q.half(), K.half(), V.half()
+    rows = list(range(0, N, 389)) + [N - 1]
+    want = oracle.attention(Q, K, V, 1.0, causal=causal, rows=rows)
+    Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+    for order in ORDERS:
+        got = sa.attn_fwd(Qd, Kd, Vd, scale=1.0, causal=causal, scan_order=order, o_dtype=torch.float32)
+        narrow = sa.attn_fwd_variant(Qd, Kd, Vd, scale=1.0, causal=causal, scan_order=order, o_dtype=torch.float32,
+                                     variant=sa.variant(rows_per_wavefront=32))
+        torch.cuda.synchronize()
+        assert_close(got.double().cpu().numpy()[:, :, rows], want, f"wide default causal={causal} {order}")
+        assert_close(got.double().cpu().numpy(), narrow.double().cpu().numpy(), f"wide vs 32 rows causal={causal} {order}")

@@ -81,7 +81,7 @@ def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
         for (head, t, first, last) in recs:
             assert (head, t) not in seen
             seen[(head, t)] = wg
-            n_kv = -(-min((t + 1) * 128, N) // 64) if causal else -(-N // 64)
+            n_kv = -(-min((t + 1) * geo["tile_q"], N) // 64) if causal else -(-N // 64)
             assert {first, last} == {0, n_kv - 1}             # the whole visible range, one direction
     assert set(seen) == {(h, t) for h in range(B * H) for t in range(geo["q_tiles"])}
     # a head's tiles stay inside the domains it is assigned to, and workgroups of one domain that
@@ -98,6 +98,8 @@ def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
 VARIANTS = [dict(decode="linear"), dict(launch="grid"), dict(launch="grid", tiles_per_workgroup=1),
             dict(launch="grid", decode="linear"), dict(launch="grid", decode="linear", tiles_per_workgroup=1),
             dict(slots_per_domain=1), dict(slots_per_domain=5), dict(decode="linear", slots_per_domain=7)]
+WIDE_VARIANTS = [dict(rows_per_wavefront=64), dict(rows_per_wavefront=64, launch="grid"),
+                 dict(rows_per_wavefront=64, decode="linear", slots_per_domain=3), dict(rows_per_wavefront=32)]
 
 
 @pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
@@ -113,7 +115,7 @@ def test_schedule_oracle_variants_cover_every_tile_once(B, H, N, causal, kw):
         for i, (head, t, first, last) in enumerate(recs):
             assert (head, t) not in seen
             seen.add((head, t))
-            n_kv = -(-min((t + 1) * 128, N) // 64) if causal else -(-N // 64)
+            n_kv = -(-min((t + 1) * geo["tile_q"], N) // 64) if causal else -(-N // 64)
             assert {first, last} == {0, n_kv - 1}
             if kw.get("launch") == "grid" or kw.get("decode") == "linear":
                 assert (first > last) == (i % 2 == 1 and n_kv > 1)     # own iteration parity
@@ -150,10 +152,26 @@ def test_schedule_oracle_hand_example():
     """B*H = 8, N = 128*130: one head per domain, 64 slots, 3 rounds (64 + 64 + 2 tiles).
     Slot 5 of domain 3: round 0 -> tile 5 forward; round 1 (reverse hand-out) -> tile 64 + 58
     backward; round 2 (2 tiles, forward hand-out) -> nothing."""
-    s = so.schedule(1, 8, 128 * 130, False, "sawtooth")
+    s = so.schedule(1, 8, 128 * 130, False, "sawtooth", rows_per_wavefront=32)
     n_kv = 128 * 130 // 64
     assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 64 + 58, n_kv - 1, 0)]
     assert s[1 * 8 + 3] == [(3, 1, 0, n_kv - 1), (3, 64 + 62, n_kv - 1, 0), (3, 129, 0, n_kv - 1)]
+
+
+def test_schedule_oracle_hand_example_wide_tiles():
+    """Same with 64 rows per wavefront, which is the default at d = 128 for this length: N = 256*70 gives 70
+    tiles of 256 rows, 32 slots, 3 rounds (32 + 32 + 6).  Slot 5 of domain 3: tile 5 forward, tile 32 + 26
+    backward, tile 64 + 5 forward; slot 7 has no third tile."""
+    assert so.launch_geometry(1, 8, 256 * 70)["tile_q"] == 256 and so.launch_geometry(1, 8, 256 * 70)["slots"] == 32
+    s = so.schedule(1, 8, 256 * 70, False, "sawtooth")
+    n_kv = 256 * 70 // 64
+    assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 58, n_kv - 1, 0), (3, 69, 0, n_kv - 1)]
+    assert s[7 * 8 + 3] == [(3, 7, 0, n_kv - 1), (3, 56, n_kv - 1, 0)]
+    # shorter sequences, head dimension 64, or a request for more than 32 workgroups per domain keep 128-row tiles
+    assert so.launch_geometry(1, 8, 256 * 63)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 70, d=64)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 70, slots_per_domain=64)["tile_q"] == 128
+    assert so.launch_geometry(1, 1, 256 * 8 * 64)["tile_q"] == 256      # one head over all 8 domains: 64 tiles each
 
 
 # ------------------------------------------------------------------ host plan == oracle
@@ -166,6 +184,7 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
         geo = so.launch_geometry(B, H, N, d=d)
         assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
         assert info["parts_per_head"] == geo["parts"] and info["q_tiles_per_head"] == geo["q_tiles"]
+        assert info["tile_q"] == geo["tile_q"]
         trace, count = sa.attn_fwd_plan(B, H, N, d, causal, order)
         want = so.schedule(B, H, N, causal, order, d=d)
         for wg in range(info["grid"]):
@@ -190,12 +209,38 @@ def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
             assert got == want[wg], f"workgroup {wg} {order}"
 
 
+@pytest.mark.parametrize("kw", WIDE_VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N", SHAPES)
+def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, causal, kw):
+    var = sa.variant(**kw)
+    info = sa.attn_fwd_launch_info(B, H, N, 128, causal, var)
+    geo = so.launch_geometry(B, H, N, d=128, **kw)
+    assert info["tile_q"] == geo["tile_q"] == 4 * kw["rows_per_wavefront"]
+    assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"] and info["q_tiles_per_head"] == geo["q_tiles"]
+    trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, "sawtooth", var)
+    want = so.schedule(B, H, N, causal, "sawtooth", d=128, **kw)
+    seen = set()
+    for wg in range(info["grid"]):
+        got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
+        assert got == want[wg], f"workgroup {wg}"
+        seen |= {(h, t) for (h, t, _, _) in got}
+    assert seen == {(h, t) for h in range(B * H) for t in range(geo["q_tiles"])}
+
+
 def test_variant_fields_are_validated(sa):
     for bad in (dict(launch=2), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
                 dict(tiles_per_workgroup=3)):
         with pytest.raises(binding.SawattnError) as e:
             sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(**bad))
         assert e.value.code == binding.ERR_INVALID_ARG and "variant." in str(e.value)
+    with pytest.raises(binding.SawattnError) as e:
+        sa.attn_fwd_launch_info(1, 8, 2048, 64, False, sa.variant(rows_per_wavefront=64))
+    assert e.value.code == binding.ERR_UNSUPPORTED
+    with pytest.raises(binding.SawattnError):
+        sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64, slots_per_domain=33))
+    with pytest.raises(binding.SawattnError):
+        sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=48))
     assert sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=96))["slots"] == 96
     with pytest.raises(binding.SawattnError):
         sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=97))
