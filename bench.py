@@ -164,7 +164,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal)
+    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype)
     orders = ["sawtooth", "cyclic"] if args.scan_order == "both" else [args.scan_order]
     # Bring the chip to the clock it sustains under this kernel before anything is timed: it leaves idle at a low
     # clock and settles, under matrix load, well below its peak clock within some tens of milliseconds.  Without

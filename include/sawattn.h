@@ -99,9 +99,10 @@ typedef struct sawattn_variant {
                                 0 = default (2).  Ignored by the persistent launch. */
     int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
                                 64 (d = 128 only): 256 rows, one workgroup per CU (at most 32 per XCD), every
-                                K/V fragment read from LDS feeds two MFMAs; 0 = default: 64 when d = 128 and
-                                every workgroup of an XCD gets at least two 256-row tiles of a head
-                                (ceil(ceil(N/256) / parts_per_head) >= 64) and slots_per_domain <= 32, else 32. */
+                                K/V fragment read from LDS feeds two MFMAs; 0 = default: 64 for d = 128,
+                                binary16 inputs, slots_per_domain <= 32 and sequences long enough that every
+                                workgroup of an XCD gets at least two 256-row tiles of a head (four under the
+                                causal mask): ceil(ceil(N/256) / parts_per_head) >= 64 (128); else 32. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round
@@ -144,9 +145,10 @@ typedef struct sawattn_launch_info {
 /*
  * attn_fwd_launch_info -- report the geometry attn_fwd (variant NULL) or attn_fwd_variant would use
  * (paper Sec. 2.2, Alg. 2 / Alg. 3: grid size and work decode).  `variant` and `out` are host memory.
- * Validates B, H, N, d and the variant like attn_fwd_variant.  Launches nothing.
+ * Validates B, H, N, d, in_dtype and the variant like attn_fwd_variant (the input type takes part in the
+ * default choice of rows per wavefront).  Launches nothing.
  */
-int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_variant* variant,
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,
                          sawattn_launch_info* out);
 
 /*
@@ -157,10 +159,10 @@ int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_v
  *   trace        host, written: int32 [grid][max_local_tiles][4], same record layout as
  *                attn_fwd_variant; unused records are left untouched.
  *   trace_count  host, written: int32 [grid].
- * B, H, N, d, causal, scan_order and the variant are validated like attn_fwd_variant.
+ * B, H, N, d, causal, scan_order, in_dtype and the variant are validated like attn_fwd_variant.
  */
-int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const sawattn_variant* variant,
-                  int32_t* trace, int32_t* trace_count);
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in_dtype,
+                  const sawattn_variant* variant, int32_t* trace, int32_t* trace_count);
 
 /*
  * sawattn_mfma_probe -- measurement aid for the roofline (paper Sec. 4.2 / 4.3 report throughput;

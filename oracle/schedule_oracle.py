@@ -37,6 +37,10 @@ from math import gcd
 T_Q, T_KV, DOMAINS = 128, 64, 8
 
 
+def ceil_div(a: int, b: int) -> int:
+    return -(-a // b)
+
+
 def resident_slots(d: int, rows_per_wavefront: int = 32) -> int:
     """Workgroups of one domain that run at the same time: 32 CUs x 3 per CU at d = 64, x 2 at d = 128,
     x 1 when a wavefront holds 64 query rows."""
@@ -45,24 +49,22 @@ def resident_slots(d: int, rows_per_wavefront: int = 32) -> int:
     return 96 if d == 64 else 64
 
 
-def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0) -> int:
+def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0, causal: bool = False,
+                           dtype: str = "f16") -> int:
     """The library's choice when the caller leaves it open: 64 rows per wavefront (256-row tiles) at d = 128
-    if every workgroup of a domain then still gets two tiles of a head, and the caller did not ask for
-    more workgroups per domain than fit that way."""
-    if d != 128 or slots_per_domain > 32:
+    with fp16 inputs if every workgroup of a domain then still gets two tiles of a head (four under the causal
+    mask), and the caller did not ask for more workgroups per domain than fit that way."""
+    if d != 128 or dtype != "f16" or slots_per_domain > 32:
         return 32
     parts = DOMAINS // gcd(heads, DOMAINS)
-    return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= 64 else 32
-
-
-def ceil_div(a: int, b: int) -> int:
-    return -(-a // b)
+    return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= (128 if causal else 64) else 32
 
 
 def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",
-                    slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128, rows_per_wavefront: int = 0):
+                    slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128, rows_per_wavefront: int = 0,
+                    causal: bool = False, dtype: str = "f16"):
     heads = B * H
-    rows = rows_per_wavefront or rows_per_wavefront_for(heads, N, d, slots_per_domain)
+    rows = rows_per_wavefront or rows_per_wavefront_for(heads, N, d, slots_per_domain, causal, dtype)
     tile_q = T_Q * rows // 32
     slots_per_domain = slots_per_domain or resident_slots(d, rows)
     q_tiles = ceil_div(N, tile_q)
@@ -107,10 +109,11 @@ def record(head: int, t: int, N: int, causal: bool, backward: bool, tile_q: int 
 
 def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str = "persistent",
              decode: str = "domain", slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128,
-             rows_per_wavefront: int = 0):
+             rows_per_wavefront: int = 0, dtype: str = "f16"):
     """Return {workgroup: [(head, query tile, first K/V tile, last K/V tile), ...]} in the order
     each workgroup processes its tiles."""
-    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d, rows_per_wavefront)
+    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d, rows_per_wavefront,
+                          causal, dtype)
     heads, parts, slots, grid, tq = B * H, geo["parts"], geo["slots"], geo["grid"], geo["tile_q"]
     saw = scan_order == "sawtooth"
     out = {}

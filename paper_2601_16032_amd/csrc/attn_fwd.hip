@@ -276,9 +276,53 @@ struct ReadAddr {
     }
 };
 
+// MFMAs of the wide variant, written out so that the register file of every operand is fixed: with
+// more than 256 registers per wavefront the accumulation registers (AccVGPRs) have to hold what only
+// the matrix pipe touches -- the O^T accumulators and the Q^T fragments -- and nothing the vector ALU
+// reads, or every use costs a copy.  The compiler does not see these as MFMAs and inserts no wait
+// states for them; mfma_settle_*() is placed wherever the vector ALU reads an accumulator that the
+// few preceding instructions may still be writing (8 passes + 3 wait states).
+template <bool BF16>
+__device__ __forceinline__ void mfma_s_first(f16v& acc, u4 k_frag, const u4& q_frag) {
+    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_frag), "a"(q_frag));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_frag), "a"(q_frag));
+}
+template <bool BF16>
+__device__ __forceinline__ void mfma_s(f16v& acc, u4 k_frag, const u4& q_frag) {
+    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
+}
+__device__ __forceinline__ void mfma_o(f16v& acc, s8 v_frag, const u4& p_frag) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_frag), "v"(p_frag));
+}
+// The accumulators pass through the statement, so that no use of them can be scheduled ahead of it.
+__device__ __forceinline__ void mfma_settle_v(f16v& a0, f16v& a1, f16v& a2, f16v& a3) {
+    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0), "+v"(a1), "+v"(a2), "+v"(a3));
+}
+__device__ __forceinline__ void mfma_settle_v(f16v& a0, f16v& a1) {
+    asm volatile("s_nop 15\n\ts_nop 3" : "+v"(a0), "+v"(a1));
+}
+template <int NACC>
+__device__ __forceinline__ void mfma_settle_a(f16v (&acc)[NACC]) {
+    asm volatile("s_nop 15\n\ts_nop 3" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) asm volatile("" : "+a"(acc[i]));
+}
+// The other direction: accumulators that vector instructions (or the compiler's copies into accumulation
+// registers) may just have written are placed in their register file here, and the MFMAs that read them
+// start a few wait states later.
+template <int NACC>
+__device__ __forceinline__ void mfma_guard(f16v (&acc)[NACC]) {
+#pragma unroll
+    for (int i = 0; i < NACC; ++i) asm volatile("" : "+a"(acc[i]));
+    asm volatile("s_nop 7" ::: "memory");
+}
+
 // One K/V tile for one wavefront out of the LDS buffers `ra` points at: S^T = K Q^T, softmax
 // update, O^T += V^T P^T.
-template <int D, bool BF16, bool CAUSAL, bool MASKED>
+// WIDE: the tile state is the wide variant's -- Q^T fragments and O^T accumulators live in accumulation
+// registers and the MFMAs are the written-out ones.
+template <int D, bool BF16, bool CAUSAL, bool MASKED, bool WIDE = false>
 __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>& ra, float c, int kv0, int qrow, int lane,
                                              int N) {
     using G = Geo<D>;
@@ -301,10 +345,21 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
                 a[ks + 2][0] = *(LDS_PTR(u4))(size_t)(ra.k[ks + 2]);
                 a[ks + 2][1] = *(LDS_PTR(u4))(size_t)(ra.k[ks + 2] + 32 * G::kRowBytes);
             }
-            s[0] = mfma_16bit<BF16>(a[ks][0], st.qf[ks], s[0]);
-            s[1] = mfma_16bit<BF16>(a[ks][1], st.qf[ks], s[1]);
+            if constexpr (WIDE) {
+                if (ks == 0) {
+                    mfma_s_first<BF16>(s[0], a[ks][0], st.qf[ks]);
+                    mfma_s_first<BF16>(s[1], a[ks][1], st.qf[ks]);
+                } else {
+                    mfma_s<BF16>(s[0], a[ks][0], st.qf[ks]);
+                    mfma_s<BF16>(s[1], a[ks][1], st.qf[ks]);
+                }
+            } else {
+                s[0] = mfma_16bit<BF16>(a[ks][0], st.qf[ks], s[0]);
+                s[1] = mfma_16bit<BF16>(a[ks][1], st.qf[ks], s[1]);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (WIDE) mfma_settle_v(s[0], s[1]);
     }
     // ---- mask: keys at or beyond N, and keys after the query under the causal mask
     unsigned masked = 0u;
@@ -373,16 +428,19 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
         };
         s8 av[NSTEP];
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (WIDE) mfma_guard(st.o);
 #pragma unroll
         for (int idx = 0; idx < AHEAD; ++idx) av[idx] = read_a(idx);
 #pragma unroll
         for (int idx = 0; idx < NSTEP; ++idx) {
             if (idx + AHEAD < NSTEP) av[idx + AHEAD] = read_a(idx + AHEAD);
             const int ks = idx / DB, db = idx % DB;
-            st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[ks]),
-                                                              st.o[db], 0, 0, 0);
+            if constexpr (WIDE) mfma_o(st.o[db], av[idx], pf[ks]);
+            else st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, av[idx]), __builtin_bit_cast(h8, pf[ks]),
+                                                                   st.o[db], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (WIDE) mfma_settle_a(st.o);
     }
 }
 
@@ -433,7 +491,7 @@ __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const Lane
 #pragma unroll
         for (int h = 0; h < NH; ++h) {   // half h: query rows qw0 + 32h .. +31 (this lane: qrow + 32h)
             const bool active = qw0 + 32 * h < N && (!CAUSAL || kv0 <= qw0 + 32 * h + 31);
-            if (active) compute_tile<D, BF16, CAUSAL, MASKED>(st[h], ra, c, kv0, qrow + 32 * h, lane, N);
+            if (active) compute_tile<D, BF16, CAUSAL, MASKED, NH == 2>(st[h], ra, c, kv0, qrow + 32 * h, lane, N);
         }
         ra.flip(cur ? -G::kTile : G::kTile);
         if (more) {
@@ -710,27 +768,6 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
 // power limited, that is where the remaining throughput is.  With one wavefront per SIMD there is
 // no second wavefront to hide latencies behind, so K and V are fetched three tiles ahead into four
 // LDS buffers each and a fetch has two whole iterations to land.
-// MFMAs of the wide variant, written out so that the register file of every operand is fixed: with
-// more than 256 registers per wavefront the accumulation registers (AccVGPRs) have to hold what only
-// the matrix pipe touches -- the O^T accumulators and the Q^T fragments -- and nothing the vector ALU
-// reads, or every use costs a copy.  The compiler does not see these as MFMAs and inserts no wait
-// states for them; mfma_settle() is placed wherever the vector ALU reads an accumulator that the
-// few preceding instructions may still be writing (8 passes + 3 wait states).
-template <bool BF16>
-__device__ __forceinline__ void mfma_s_first(f16v& acc, u4 k_frag, const u4& q_frag) {
-    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_frag), "a"(q_frag));
-    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(acc) : "v"(k_frag), "a"(q_frag));
-}
-template <bool BF16>
-__device__ __forceinline__ void mfma_s(f16v& acc, u4 k_frag, const u4& q_frag) {
-    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
-    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
-}
-__device__ __forceinline__ void mfma_o(f16v& acc, s8 v_frag, const u4& p_frag) {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_frag), "v"(p_frag));
-}
-__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
-
 constexpr int kWideBuffers = 4;
 constexpr int kWideLdsBytes = 2 * kWideBuffers * Geo<128>::kTile;
 
@@ -755,12 +792,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     u4 vreg[NL];        // bfloat16 V chunks in flight (BF16 only)
     float e0[2][16], e1[2][16];
     float tmax_ahead[2] = {0.f, 0.f};
-    // The Q^T fragments move to accumulation registers for the duration of the range (and back at its end).
-    u4 qa[2][KS];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "=a"(qa[h][ks]) : "0"(st[h].qf[ks]));
+    mfma_guard(st[0].o);
+    mfma_guard(st[1].o);
 
     // Tile i of the range lives in K buffer i & 3 and V buffer i & 3.  Fetches beyond the range re-fetch its
     // last tile into a buffer nobody reads, which keeps the loop free of special cases.
@@ -844,14 +877,14 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             if (m + RA < NA) a[m + RA] = *(LDS_PTR(u4))(size_t)(rk[(m + RA) / 2] - G::kTile + ((m + RA) & 1) * 32 * G::kRowBytes);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
-                else mfma_s<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
+                if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
+                else mfma_s<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int m = 0; m < RA; ++m) ak[m] = k_read(m);
-        mfma_settle();
+        mfma_settle_v(A[0][0], A[0][1], A[1][0], A[1][1]);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             float mx = fmaxf(A[h][0][0], A[h][0][1]);
@@ -861,6 +894,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + kRescaleSlack)) != 0) rescale(h, tmax);
             shifted_scores(h);
         }
+        mfma_guard(st[0].o);
+        mfma_guard(st[1].o);
     }
 
     // ---------------------------------------------------------------- steady state: iteration i
@@ -904,8 +939,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                 else av[m + RA - NA] = v_read(m + RA - NA);    // the first V^T fragments of the second product
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
-                    else mfma_s<BF16>(A[h][m & 1], a[m], qa[h][m / 2]);
+                    if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
+                    else mfma_s<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
                     exp_unit(h, m);
                     if (h == 0 && (m & 1) == 0) {
                         constexpr_fetch(m / 2);      // 8 loads over 16 fragments
@@ -998,7 +1033,9 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         return need;
     };
     auto raise_reference = [&]() {
-        mfma_settle();
+        mfma_settle_v(A[0][0], A[0][1], A[1][0], A[1][1]);
+        mfma_settle_a(st[0].o);
+        mfma_settle_a(st[1].o);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             if (__builtin_amdgcn_ballot_w64(!(tmax_ahead[h] <= st[h].M + kRescaleSlack)) != 0) {
@@ -1006,6 +1043,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                 shifted_scores(h);
             }
         }
+        mfma_guard(st[0].o);
+        mfma_guard(st[1].o);
     };
     int i = 0;
     while (i + 1 < count) {
@@ -1033,11 +1072,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    mfma_settle();     // the accumulators are complete before the caller's vector code reads them
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "=v"(st[h].qf[ks]) : "0"(qa[h][ks]));
+    mfma_settle_a(st[0].o);   // the accumulators are complete before the caller's vector code reads them
+    mfma_settle_a(st[1].o);
     wait_tile_landed();   // also the fetches past the end of the range
     __syncthreads();      // all reads of the last tile are done before anything refills the buffers
 }
@@ -1071,7 +1107,8 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         for (int ks = 0; ks < KS; ++ks) {
             u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
             v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
-            st[h].qf[ks] = v;
+            if constexpr (NH == 2) asm volatile("" : "=a"(st[h].qf[ks]) : "0"(v));   // accumulation registers from here on
+            else st[h].qf[ks] = v;
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -1324,7 +1361,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 }
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
-int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant* v, Schedule* out) {
+int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out) {
     int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
@@ -1336,7 +1373,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant*
         if (v->rows_per_wavefront == 64 && d != 128)
             return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
         rows = v->rows_per_wavefront;
-        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d);
+        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16);
         if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : kTileQ))
             return fail(SAWATTN_ERR_INVALID_ARG,
                         "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per wavefront)");
@@ -1347,7 +1384,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, const sawattn_variant*
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
     }
-    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d);
+    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
     const int tile_q = rows == 64 ? 2 * kTileQ : kTileQ;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q);
@@ -1358,9 +1395,6 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         int scan_order, int in_dtype, int o_dtype, void* hip_stream, const sawattn_variant* variant, int32_t* trace,
         int32_t* trace_count) {
     int rc = check_shape(B, H, N, d);
-    if (rc != SAWATTN_OK) return rc;
-    Schedule sched;
-    rc = schedule_for(B, H, N, d, causal != 0, variant, &sched);
     if (rc != SAWATTN_OK) return rc;
     if (!Q || !K || !V || !O) return fail(SAWATTN_ERR_INVALID_ARG, "Q, K, V and O must be non-null");
     if (((uintptr_t)Q | (uintptr_t)K | (uintptr_t)V | (uintptr_t)O) & 15u)
@@ -1374,6 +1408,9 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         return fail(SAWATTN_ERR_INVALID_ARG, "o_dtype must be SAWATTN_F16, SAWATTN_BF16 or SAWATTN_F32");
     if ((trace == nullptr) != (trace_count == nullptr))
         return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be given together");
+    Schedule sched;
+    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &sched);
+    if (rc != SAWATTN_OK) return rc;
     {   // A workgroup writes its O rows while others still read Q, K, V: O may not share memory with them.
         const unsigned long long elems = (unsigned long long)B * H * N * d;
         const unsigned long long in_bytes = elems * 2u, out_bytes = elems * (o_dtype == SAWATTN_F32 ? 4u : 2u);
@@ -1426,28 +1463,32 @@ int attn_fwd_variant(const void* Q, const void* K, const void* V, void* O, int B
                         trace_count);
 }
 
-int attn_fwd_launch_info(int B, int H, int N, int d, int causal, const sawattn_variant* variant,
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,
                          sawattn_launch_info* out) {
     if (!out) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "out must be non-null");
+    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
+        return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
     int rc = sawattn::check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     sawattn::Schedule s;
-    rc = sawattn::schedule_for(B, H, N, d, causal != 0, variant, &s);
+    rc = sawattn::schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     sawattn::fill_info(s, d, out);
     return SAWATTN_OK;
 }
 
-int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, const sawattn_variant* variant,
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in_dtype, const sawattn_variant* variant,
                   int32_t* trace, int32_t* trace_count) {
     using namespace sawattn;
     if (!trace || !trace_count) return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be non-null");
+    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
+        return fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
     if (scan_order != SAWATTN_SCAN_CYCLIC && scan_order != SAWATTN_SCAN_SAWTOOTH)
         return fail(SAWATTN_ERR_INVALID_ARG, "scan_order must be SAWATTN_SCAN_CYCLIC or SAWATTN_SCAN_SAWTOOTH");
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     Schedule s;
-    rc = schedule_for(B, H, N, d, causal != 0, variant, &s);
+    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     // the kernel's outer loop, one workgroup at a time
     for (int wg = 0; wg < s.grid; ++wg) {

@@ -44,13 +44,16 @@ constexpr int kMaxSlots = 96;    // largest number of workgroups per domain for 
 // Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
 // dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for two.
 // Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
-// workgroup tiles) for head dimension 128 once every resident workgroup of a domain gets at least two
-// tiles of a head, i.e. where the steady state dominates; 32 rows otherwise.
-SAW_HD int default_rows_per_wavefront(int heads, int N, int d) {
-    if (d != 128) return 32;
+// workgroup tiles) for head dimension 128 and binary16 inputs once the steady state dominates, i.e.
+// every resident workgroup of a domain gets at least two full-length tiles of a head (four under the
+// causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured: +3.5 to
+// +4.5 % there; with bfloat16 inputs the V conversion makes the wide variant's single instruction
+// stream longer and it only pays from about 64K keys on.)
+SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16) {
+    if (d != 128 || bf16) return 32;
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
-    return (wide_tiles + parts - 1) / parts >= 64 ? 64 : 32;
+    return (wide_tiles + parts - 1) / parts >= (causal ? 128 : 64) ? 64 : 32;
 }
 
 // The wide variant (256-row tiles, up to 512 registers per wavefront) runs one workgroup per CU.

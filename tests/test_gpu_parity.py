@@ -238,7 +238,7 @@ def test_scan_orders_agree_small(sa, cfg):
 @pytest.mark.parametrize("order", ORDERS)
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N,d", [(1, 8, 128 * 70, 128), (1, 8, 128 * 100, 64), (2, 3, 333, 128), (1, 32, 4096, 128),
-                                     (1, 1, 256, 64)])
+                                     (1, 1, 256, 64), (1, 8, 256 * 64 + 10, 128)])
 def test_device_schedule_matches_oracle(sa, B, H, N, d, causal, order):
     """Every workgroup records the query tile it took at each local iteration and the first / last
     K/V tile it visited; bit-exact against the schedule oracle (Alg. 2 + Alg. 4 per cache domain)."""
@@ -278,7 +278,7 @@ def test_variants_schedule_and_output(sa, oracle, kw, causal):
             O, trace, count = sa.attn_fwd_variant(Q, K, V, scale=scale, causal=causal, scan_order=order,
                                                   o_dtype=torch.float32, variant=var, trace=True)
             torch.cuda.synchronize()
-            want = so.schedule(B, H, N, causal, order, d=d, **kw)
+            want = so.schedule(B, H, N, causal, order, d=d, dtype=dtype, **kw)
             trace, count = trace.cpu(), count.cpu()
             assert trace.shape[0] == len(want)
             for wg, recs in want.items():
@@ -333,7 +333,7 @@ def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal):
     """A sequence long enough that the library picks 64 rows per wavefront by itself (two rounds of 32 slots per
     head), with score levels that jump from tile to tile so that the reference maximum is raised again and
     again in both scan directions; checked on sampled rows, and against the explicit 32-row variant."""
-    H, N, d = 8, 256 * 64 + 100, 128
+    H, N, d = 8, (256 * 128 if causal else 256 * 64) + 100, 128
     assert sa.attn_fwd_launch_info(1, H, N, d, causal)["tile_q"] == 256
     g = torch.Generator("cpu").manual_seed(99)
     level = 60.0 * torch.rand(H, (N + 63) // 64, generator=g)

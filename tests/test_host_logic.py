@@ -75,7 +75,7 @@ SHAPES = [(1, 1, 256), (1, 8, 2048), (1, 16, 8192), (1, 32, 16384), (4, 32, 3276
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
     sched = so.schedule(B, H, N, causal, "sawtooth")
-    geo = so.launch_geometry(B, H, N)
+    geo = so.launch_geometry(B, H, N, causal=causal)
     seen = {}
     for wg, recs in sched.items():
         for (head, t, first, last) in recs:
@@ -107,7 +107,7 @@ WIDE_VARIANTS = [dict(rows_per_wavefront=64), dict(rows_per_wavefront=64, launch
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_schedule_oracle_variants_cover_every_tile_once(B, H, N, causal, kw):
     sched = so.schedule(B, H, N, causal, "sawtooth", **kw)
-    geo = so.launch_geometry(B, H, N, **kw)
+    geo = so.launch_geometry(B, H, N, causal=causal, **kw)
     assert len(sched) == geo["grid"] and geo["grid"] % 8 == 0
     seen = set()
     for wg, recs in sched.items():
@@ -142,7 +142,7 @@ def test_schedule_gives_every_workgroup_the_same_number_of_tile_steps(sa, B, H, 
     """On the benchmark shapes every workgroup walks the same number of K/V tiles in total: causal
     tiles (tile i costs i+1) are paired long with short inside a head when it has an even number
     of rounds, across two heads when it has one round (workload 3)."""
-    trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, "sawtooth")
+    trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, "sawtooth", dtype="bf16" if causal else "f16")
     cost = [sum(abs(int(a) - int(b)) + 1 for (_, _, a, b) in trace[wg, : int(count[wg])].tolist())
             for wg in range(trace.shape[0])]
     assert max(cost) == min(cost)
@@ -167,9 +167,13 @@ def test_schedule_oracle_hand_example_wide_tiles():
     n_kv = 256 * 70 // 64
     assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 58, n_kv - 1, 0), (3, 69, 0, n_kv - 1)]
     assert s[7 * 8 + 3] == [(3, 7, 0, n_kv - 1), (3, 56, n_kv - 1, 0)]
-    # shorter sequences, head dimension 64, or a request for more than 32 workgroups per domain keep 128-row tiles
+    # shorter sequences, head dimension 64, bfloat16 inputs, a causal mask on fewer than 128 tiles, or a request
+    # for more than 32 workgroups per domain keep 128-row tiles
     assert so.launch_geometry(1, 8, 256 * 63)["tile_q"] == 128
     assert so.launch_geometry(1, 8, 256 * 70, d=64)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 70, dtype="bf16")["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 70, causal=True)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 128, causal=True)["tile_q"] == 256
     assert so.launch_geometry(1, 8, 256 * 70, slots_per_domain=64)["tile_q"] == 128
     assert so.launch_geometry(1, 1, 256 * 8 * 64)["tile_q"] == 256      # one head over all 8 domains: 64 tiles each
 
@@ -179,17 +183,18 @@ def test_schedule_oracle_hand_example_wide_tiles():
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
-    for d in (128, 64):                      # d = 64 runs up to 96 workgroups per domain, d = 128 up to 64
-        info = sa.attn_fwd_launch_info(B, H, N, d, causal)
-        geo = so.launch_geometry(B, H, N, d=d)
+    # d = 64 runs up to 96 workgroups per domain, d = 128 up to 64, or 32 of twice the size for long fp16 inputs
+    for d, dtype in ((128, "f16"), (128, "bf16"), (64, "f16")):
+        info = sa.attn_fwd_launch_info(B, H, N, d, causal, dtype=dtype)
+        geo = so.launch_geometry(B, H, N, d=d, causal=causal, dtype=dtype)
         assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
         assert info["parts_per_head"] == geo["parts"] and info["q_tiles_per_head"] == geo["q_tiles"]
         assert info["tile_q"] == geo["tile_q"]
-        trace, count = sa.attn_fwd_plan(B, H, N, d, causal, order)
-        want = so.schedule(B, H, N, causal, order, d=d)
+        trace, count = sa.attn_fwd_plan(B, H, N, d, causal, order, dtype=dtype)
+        want = so.schedule(B, H, N, causal, order, d=d, dtype=dtype)
         for wg in range(info["grid"]):
             got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
-            assert got == want[wg], f"workgroup {wg} d={d}"
+            assert got == want[wg], f"workgroup {wg} d={d} {dtype}"
 
 
 @pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
@@ -198,7 +203,7 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
 def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
     var = sa.variant(**kw)
     info = sa.attn_fwd_launch_info(B, H, N, 64, causal, var)
-    geo = so.launch_geometry(B, H, N, d=64, **kw)
+    geo = so.launch_geometry(B, H, N, d=64, causal=causal, **kw)
     assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
     assert info["max_local_tiles"] == geo["max_local"]
     for order in ("cyclic", "sawtooth"):
@@ -215,7 +220,7 @@ def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
 def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, causal, kw):
     var = sa.variant(**kw)
     info = sa.attn_fwd_launch_info(B, H, N, 128, causal, var)
-    geo = so.launch_geometry(B, H, N, d=128, **kw)
+    geo = so.launch_geometry(B, H, N, d=128, causal=causal, **kw)
     assert info["tile_q"] == geo["tile_q"] == 4 * kw["rows_per_wavefront"]
     assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"] and info["q_tiles_per_head"] == geo["q_tiles"]
     trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, "sawtooth", var)
