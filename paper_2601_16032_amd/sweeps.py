@@ -10,7 +10,8 @@ restates.
 
 Studies
   seqlen    Sec. 3.2 / 3.3: sequence length 2K...128K at B=1, H in {1, 8}, d in {64, 128}:
-            L2 requests against 2NdE(1 + N/T_q), and where non-compulsory misses set in.
+            L2 requests against 2NdE(1 + N/T_q) (T_q = 128, or 256 where the library picks its wide
+            variant), and where non-compulsory misses set in.
   resident  Sec. 3.4: G = 8 w persistent workgroups, w = 1...64 (96 at d = 64) per XCD: hit rate against 1 - 1/w.
   decode    Sec. 2.2 Alg. 2 as printed (one linear stride over all XCDs) against the per-XCD decode.
   launch    Alg. 3 (direct launch, one or two query tiles per workgroup) against the persistent
@@ -30,7 +31,6 @@ from . import traffic_model as tm
 from . import workloads
 
 L2_BYTES_PER_XCD = 4 * 2 ** 20
-TILE_Q = 128
 
 
 def _pt(B, H, N, d, causal=False, order="sawtooth", **variant):
@@ -80,14 +80,14 @@ def model(pt, info):
     """What Sec. 3.2-3.4 and Sec. 4 predict for a point, in bytes."""
     B, H, N, d, causal = pt["B"], pt["H"], pt["N"], pt["d"], pt["causal"]
     kv_head = 2 * N * d * 2
-    out = {"l2_read_bytes": tm.l2_read_bytes(B, H, N, d, TILE_Q, causal),
+    out = {"l2_read_bytes": tm.l2_read_bytes(B, H, N, d, info["tile_q"], causal),
            "compulsory_bytes": tm.compulsory_bytes(B, H, N, d),
            "kv_bytes_per_head": kv_head,
            "kv_over_l2": kv_head / L2_BYTES_PER_XCD}
     if not causal and pt["variant"].get("decode", "domain") == "domain" and pt["variant"].get("launch", "persistent") == "persistent":
         # every domain that holds a part of a head walks that head's K/V once per round
         # (a domain that holds 1/parts of a head's query tiles sees them as tiles `parts` times as tall)
-        per_domain_head = tm.lru_kv_miss_bytes(N, d, TILE_Q * info["parts_per_head"], info["slots"],
+        per_domain_head = tm.lru_kv_miss_bytes(N, d, info["tile_q"] * info["parts_per_head"], info["slots"],
                                                L2_BYTES_PER_XCD, pt["order"] == "sawtooth")
         out["lru_kv_miss_bytes"] = per_domain_head * B * H * info["parts_per_head"]
         out["lockstep_hit_rate"] = 1.0 - 1.0 / info["slots"]
@@ -154,6 +154,7 @@ def main(argv=None):
         flops = 4.0 * pt["B"] * pt["H"] * pt["N"] ** 2 * pt["d"] * (0.5 if pt["causal"] else 1.0)
         n = args.warmup + args.launches
         print(json.dumps({"study": args.study, "point": i, **pt, "grid": info["grid"], "slots": info["slots"],
+                          "tile_q": info["tile_q"],
                           "parts_per_head": info["parts_per_head"], "ms_median": ms[len(ms) // 2], "ms_min": ms[0],
                           "tflops": flops / (ms[len(ms) // 2] * 1e-3) / 1e12, "model": model(pt, info),
                           "dispatches": [dispatch, dispatch + n]}), flush=True)
