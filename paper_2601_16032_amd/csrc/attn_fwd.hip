@@ -22,6 +22,10 @@
 // A query tile's scan is a software-pipelined run of full, unmasked K/V tiles (pipelined_range)
 // plus, at one end, a short run of masked tiles (general_range).  The workgroups of one XCD walk
 // the same head together and re-align between heads (domain_sync).
+//
+// For head dimension 128 there is a second tile shape (NH = 2 in the templates, pipelined_range_wide):
+// a wavefront owns two such 32-row halves, a workgroup 256 query rows, one workgroup per CU, and
+// every K / V^T fragment read from LDS feeds one MFMA per half.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
