@@ -34,15 +34,13 @@ namespace sawattn {
 
 constexpr int kTileQ = 128;      // query rows per workgroup tile (twice that in the wide variant)
 constexpr int kTileKV = 64;      // key/value rows per streamed tile
-constexpr int kThreads = 256;    // 4 wavefronts, 32 query rows each
+constexpr int kThreads = 256;    // 4 wavefronts of 32 query rows each (64 in the wide variant)
 constexpr int kDomains = 8;      // XCDs
+constexpr int kMaxSlots = 96;    // largest number of workgroups per domain for any tile shape
+
 SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } return a; }
 SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-constexpr int kMaxSlots = 96;    // largest number of workgroups per domain for any head dimension
-
-// Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
-// dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for two.
 // Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
 // workgroup tiles) for head dimension 128 and binary16 inputs once the steady state dominates, i.e.
 // every resident workgroup of a domain gets at least two full-length tiles of a head (four under the
@@ -56,7 +54,9 @@ SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool
     return (wide_tiles + parts - 1) / parts >= (causal ? 128 : 64) ? 64 : 32;
 }
 
-// The wide variant (256-row tiles, up to 512 registers per wavefront) runs one workgroup per CU.
+// Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
+// dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for
+// two; the wide variant (256-row tiles, up to 512 registers per wavefront, 128 KiB LDS) runs one.
 SAW_HD int resident_slots(int d, int tile_q = kTileQ) { return tile_q > kTileQ ? 32 : (d == 64 ? 96 : 64); }
 
 // Besides that default, the launch variants the paper describes are kept selectable so that they
