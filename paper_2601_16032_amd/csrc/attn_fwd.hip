@@ -1042,8 +1042,12 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         mfma_settle_a(st[1].o);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            if (__builtin_amdgcn_ballot_w64(!(tmax_ahead[h] <= st[h].M + kRescaleSlack)) != 0) {
-                rescale(h, tmax_ahead[h]);
+            // (the comparison is redone on a value the compiler cannot trace back into the loop, or the loop
+            // would carry both halves' results along as lane masks)
+            float t = tmax_ahead[h];
+            asm volatile("" : "+v"(t));
+            if (__builtin_amdgcn_ballot_w64(!(t <= st[h].M + kRescaleSlack)) != 0) {
+                rescale(h, t);
                 shifted_scores(h);
             }
         }
