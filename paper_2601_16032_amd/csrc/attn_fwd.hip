@@ -786,7 +786,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     constexpr int NB = 4 * DB;            // V^T fragments of one tile (each feeds two MFMAs)
     constexpr int NL = G::kLoadsPerWave;
     constexpr unsigned VB = kWideBuffers * G::kTile;   // V buffers follow the K buffers
-    constexpr int RA = 3;                 // LDS fragments are read this many fragments ahead of their MFMAs
+    constexpr int RA = 2;                 // fragments read ahead where fragments are read one by one (first and last tile)
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
     const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
@@ -937,17 +937,22 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                     if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
                 }
             };
+            // Fragments are read from LDS two at a time, one pair ahead, and used in the order second, first:
+            // the one wait for the later read covers both (half as many waits in the instruction stream).
 #pragma unroll
-            for (int m = 0; m < NA; ++m) {
-                if (m + RA < NA) a[m + RA] = k_read(m + RA);
-                else av[m + RA - NA] = v_read(m + RA - NA);    // the first V^T fragments of the second product
+            for (int q = 0; q < NA; ++q) {
+                if ((q & 1) == 0) {
+                    if (q + 2 < NA) { a[q + 2] = k_read(q + 2); a[q + 3] = k_read(q + 3); }
+                    else { av[0] = v_read(0); av[1] = v_read(1); }   // the first V^T fragments of the second product
+                }
+                const int m = q ^ 1;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
                     else mfma_s<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
-                    exp_unit(h, m);
-                    if (h == 0 && (m & 1) == 0) {
-                        constexpr_fetch(m / 2);      // 8 loads over 16 fragments
+                    exp_unit(h, q);
+                    if (h == 0 && (q & 1) == 0) {
+                        constexpr_fetch(q / 2);      // 8 loads over 16 fragments
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -969,10 +974,11 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         // (the two halves' maxima are separate dependency chains; their steps alternate)
 #pragma unroll
         for (int idx = 0; idx < HB; ++idx) {
-            av[idx + RA] = v_read(idx + RA);
+            if ((idx & 1) == 0) { av[idx + 2] = v_read(idx + 2); av[idx + 3] = v_read(idx + 3); }
+            const int f = idx ^ 1;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
+                mfma_o(st[h].o[f % DB], av[f], pf[h][f / DB]);
                 if (idx >= MS) {
 #pragma unroll
                     for (int q = 0; q < MPS; ++q) {
@@ -1001,11 +1007,14 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         constexpr int CPS = (NL * 4 + 2 * (NB - HB) - 1) / (2 * (NB - HB));   // bf16 pair conversions per slot
 #pragma unroll
         for (int idx = HB; idx < NB; ++idx) {
-            if (idx + RA < NB) av[idx + RA] = v_read(idx + RA);
-            else ak[idx + RA - NB] = k_read(idx + RA - NB);     // the first K fragments of the next iteration
+            if ((idx & 1) == 0) {
+                if (idx + 2 < NB) { av[idx + 2] = v_read(idx + 2); av[idx + 3] = v_read(idx + 3); }
+                else { ak[0] = k_read(0); ak[1] = k_read(1); }   // the first K fragments of the next iteration
+            }
+            const int f = idx ^ 1;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                mfma_o(st[h].o[idx % DB], av[idx], pf[h][idx / DB]);
+                mfma_o(st[h].o[f % DB], av[f], pf[h][f / DB]);
 #pragma unroll
                 for (int q = 0; q < FPS; ++q) {
                     const int r = (idx - HB) * FPS + q;
