@@ -251,6 +251,13 @@ __device__ __forceinline__ float pair_sum(float x) {
     return lo + hi;
 }
 
+// Adds the two binary16 values of `ph` to two float partial sums (one mixed-precision FMA each:
+// exact, and cheaper in the instruction stream than the two-element dot product).
+__device__ __forceinline__ void add_pair(float& sum_lo, float& sum_hi, h2 ph) {
+    asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]" : "+v"(sum_lo) : "v"(ph));
+    asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(sum_hi) : "v"(ph));
+}
+
 // The running maximum is only raised when a tile's maximum exceeds it by more than this many
 // binades; until then probabilities are taken relative to the older, smaller reference and may be
 // as large as 2^kRescaleSlack.  O and the running sum stay consistent, so the result is unchanged;
@@ -526,7 +533,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
     constexpr int EU = 16 / NA;           // exp units (2 exp + convert + sum of one pair) per MFMA of phase A
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
-    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    float L_hi = 0.f;   // second partial of the running sum (upper halves of the probability pairs), folded into st.L
     const f16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f16v A[2];          // S^T of the tile one ahead: block b = keys 32b..32b+31 of the tile
     float x[32];        // score*c - M of the current tile, index 16*b + r
@@ -554,6 +561,8 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     auto rescale = [&](float tmax) {
+        st.L += L_hi;
+        L_hi = 0.f;
         const float Mnew = fmaxf(st.M, tmax);
         const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st.M - Mnew);
         st.M = Mnew;
@@ -574,7 +583,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
         if (u >= 1 && u <= 16) {
             const int v = u - 1;
             const h2 ph = __builtin_convertvector(f2{e0[v], e1[v]}, h2);
-            st.L = __builtin_amdgcn_fdot2(ph, ones, st.L, false);   // sum of the rounded probabilities
+            add_pair(st.L, L_hi, ph);   // sum of the rounded probabilities, the values the second product uses
             pf[v / 4][v % 4] = __builtin_bit_cast(unsigned, ph);
         }
     };
@@ -762,6 +771,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    st.L += L_hi;
     __syncthreads();   // all reads of the last tile are done before anything refills the buffers
 }
 
@@ -789,7 +799,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     constexpr int RA = 2;                 // fragments read ahead where fragments are read one by one (first and last tile)
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
-    const h2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    float L_hi[2] = {0.f, 0.f};   // second partials of the running sums, folded into st[h].L
     f16v A[2][2];       // [half][block]: S^T of the tile one ahead
     float x[2][32];     // [half]: score*c - M of the current tile
     u4 pf[2][4];        // [half]: its probabilities as B operands
@@ -822,6 +832,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
     auto rescale = [&](int h, float tmax) {
+        st[h].L += L_hi[h];
+        L_hi[h] = 0.f;
         const float Mnew = fmaxf(st[h].M, tmax);
         const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st[h].M - Mnew);
         st[h].M = Mnew;
@@ -846,7 +858,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             e1[h][u] = fast_exp2(x[h][2 * u + 1]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (u >= 1 && u <= 16) st[h].L = __builtin_amdgcn_fdot2(ph, ones, st[h].L, false);
+        if (u >= 1 && u <= 16) add_pair(st[h].L, L_hi[h], ph);
     };
     auto shifted_scores = [&](int h) {
 #pragma unroll
@@ -1089,6 +1101,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             __builtin_amdgcn_sched_barrier(0);
         }
     }
+    st[0].L += L_hi[0];
+    st[1].L += L_hi[1];
     mfma_settle_a(st[0].o);   // the accumulators are complete before the caller's vector code reads them
     mfma_settle_a(st[1].o);
     wait_tile_landed();   // also the fetches past the end of the range
