@@ -114,22 +114,28 @@ def cpu_baseline(w, Q, K, V, target_seconds):
         fl = sum(4.0 * ((r + 1) if w.causal else w.N) * w.d for r in rows)
         return dt, fl
 
-    n0 = min(w.N, 256)
-    run(0, 0, 16)                                  # first call loads the library and starts the threads
-    dt0, fl0 = run(0, 0, n0)                       # calibration, not counted
-    rows_budget = int(n0 * target_seconds / max(dt0, 1e-4))
+    run(0, 0, min(w.N, 16))                        # first call loads the library and starts the threads
+    # Whole heads (all their query rows) one after another until the time is used up; the last head is cut to the
+    # rows that still fit, judged by the rate seen so far (first head: by a 1024-row calibration run, not counted).
+    dt0, fl0 = run(0, 0, min(w.N, 1024))
+    rate = fl0 / max(dt0, 1e-6)                    # flop per second
     total_dt = total_fl = 0.0
     rows_done, heads_done = 0, 0
+    head_fl = 4.0 * w.N * w.N * w.d * (0.5 if w.causal else 1.0)
     for idx in range(w.B * w.H):
-        left = rows_budget - rows_done
-        if left < 64:
+        left = target_seconds - total_dt
+        if left < 0.05 * target_seconds:
             break
-        n = min(w.N, left)
+        n = w.N if head_fl / rate <= left else max(64, int(w.N * left * rate / head_fl))
+        n = min(n, w.N)
         dt, fl = run(idx // w.H, idx % w.H, n)
         total_dt += dt
         total_fl += fl
         rows_done += n
         heads_done += 1
+        rate = total_fl / total_dt
+        if n < w.N:
+            break
     return {"value": total_fl / total_dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
             "sample": f"{rows_done} evenly spaced query rows over the first {heads_done} (batch, head) pairs of "
                       f"{w.name}: {total_fl:.3e} flop in {total_dt:.1f} s, fp64, full score rows",
