@@ -98,11 +98,15 @@ typedef struct sawattn_variant {
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
                                 0 = default (2).  Ignored by the persistent launch. */
     int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
-                                64 (d = 128 only): 256 rows, one workgroup per CU (at most 32 per XCD), every
-                                K/V fragment read from LDS feeds two MFMAs; 0 = default: 64 for d = 128,
-                                binary16 inputs, slots_per_domain <= 32 and sequences long enough that every
-                                workgroup of an XCD gets at least two 256-row tiles of a head (four under the
-                                causal mask): ceil(ceil(N/256) / parts_per_head) >= 64 (128); else 32. */
+                                64 (d = 128 and binary16 inputs only): 256 rows, one workgroup per CU (at most
+                                32 per XCD), every K/V fragment read from LDS feeds two MFMAs, and
+                                scale*log2(e) is folded into Q, rounded to binary16 (a relative error of
+                                2^-11 per element of Q on top of the rounding the inputs already carry: it
+                                grows with the size of the scores; UNSUPPORTED for bfloat16 inputs);
+                                0 = default: 64 for d = 128, binary16 inputs, |scale| <= 2/sqrt(d),
+                                slots_per_domain <= 32 and sequences long enough that every workgroup of an
+                                XCD gets at least two 256-row tiles of a head (four under the causal mask):
+                                ceil(ceil(N/256) / parts_per_head) >= 64 (128); else 32. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round
@@ -145,11 +149,11 @@ typedef struct sawattn_launch_info {
 /*
  * attn_fwd_launch_info -- report the geometry attn_fwd (variant NULL) or attn_fwd_variant would use
  * (paper Sec. 2.2, Alg. 2 / Alg. 3: grid size and work decode).  `variant` and `out` are host memory.
- * Validates B, H, N, d, in_dtype and the variant like attn_fwd_variant (the input type takes part in the
- * default choice of rows per wavefront).  Launches nothing.
+ * Validates B, H, N, d, scale, in_dtype and the variant like attn_fwd_variant (the input type and the
+ * scale take part in the default choice of rows per wavefront).  Launches nothing.
  */
-int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,
-                         sawattn_launch_info* out);
+int attn_fwd_launch_info(int B, int H, int N, int d, float scale, int causal, int in_dtype,
+                         const sawattn_variant* variant, sawattn_launch_info* out);
 
 /*
  * attn_fwd_plan -- the schedule attn_fwd_variant would run, computed on the host from the same work
@@ -159,9 +163,9 @@ int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int in_dtype, c
  *   trace        host, written: int32 [grid][max_local_tiles][4], same record layout as
  *                attn_fwd_variant; unused records are left untouched.
  *   trace_count  host, written: int32 [grid].
- * B, H, N, d, causal, scan_order, in_dtype and the variant are validated like attn_fwd_variant.
+ * B, H, N, d, scale, causal, scan_order, in_dtype and the variant are validated like attn_fwd_variant.
  */
-int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in_dtype,
+int attn_fwd_plan(int B, int H, int N, int d, float scale, int causal, int scan_order, int in_dtype,
                   const sawattn_variant* variant, int32_t* trace, int32_t* trace_count);
 
 /*

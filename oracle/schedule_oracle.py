@@ -50,11 +50,12 @@ def resident_slots(d: int, rows_per_wavefront: int = 32) -> int:
 
 
 def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0, causal: bool = False,
-                           dtype: str = "f16") -> int:
+                           dtype: str = "f16", scale: float = None) -> int:
     """The library's choice when the caller leaves it open: 64 rows per wavefront (256-row tiles) at d = 128
-    with fp16 inputs if every workgroup of a domain then still gets two tiles of a head (four under the causal
-    mask), and the caller did not ask for more workgroups per domain than fit that way."""
-    if d != 128 or dtype != "f16" or slots_per_domain > 32:
+    with fp16 inputs and |scale| <= 2/sqrt(d) (None: the usual 1/sqrt(d)) if every workgroup of a domain then
+    still gets two tiles of a head (four under the causal mask), and the caller did not ask for more
+    workgroups per domain than fit that way."""
+    if d != 128 or dtype != "f16" or slots_per_domain > 32 or (scale is not None and scale * scale * d > 4.0):
         return 32
     parts = DOMAINS // gcd(heads, DOMAINS)
     return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= (128 if causal else 64) else 32
@@ -62,9 +63,9 @@ def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0
 
 def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",
                     slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128, rows_per_wavefront: int = 0,
-                    causal: bool = False, dtype: str = "f16"):
+                    causal: bool = False, dtype: str = "f16", scale: float = None):
     heads = B * H
-    rows = rows_per_wavefront or rows_per_wavefront_for(heads, N, d, slots_per_domain, causal, dtype)
+    rows = rows_per_wavefront or rows_per_wavefront_for(heads, N, d, slots_per_domain, causal, dtype, scale)
     tile_q = T_Q * rows // 32
     slots_per_domain = slots_per_domain or resident_slots(d, rows)
     q_tiles = ceil_div(N, tile_q)
@@ -109,11 +110,11 @@ def record(head: int, t: int, N: int, causal: bool, backward: bool, tile_q: int 
 
 def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str = "persistent",
              decode: str = "domain", slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128,
-             rows_per_wavefront: int = 0, dtype: str = "f16"):
+             rows_per_wavefront: int = 0, dtype: str = "f16", scale: float = None):
     """Return {workgroup: [(head, query tile, first K/V tile, last K/V tile), ...]} in the order
     each workgroup processes its tiles."""
     geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d, rows_per_wavefront,
-                          causal, dtype)
+                          causal, dtype, scale)
     heads, parts, slots, grid, tq = B * H, geo["parts"], geo["slots"], geo["grid"], geo["tile_q"]
     saw = scan_order == "sawtooth"
     out = {}

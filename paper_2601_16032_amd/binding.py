@@ -6,6 +6,7 @@ library has not been built, loading raises.  PyTorch is used for device memory a
 from __future__ import annotations
 
 import ctypes
+import math
 import os
 
 import torch
@@ -78,9 +79,9 @@ def lib() -> ctypes.CDLL:
         L.attn_fwd_variant.restype = ci
         L.attn_fwd_variant.argtypes = L.attn_fwd.argtypes + [pv, vp, vp]
         L.attn_fwd_launch_info.restype = ci
-        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ci, pv, ctypes.POINTER(LaunchInfo)]
+        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, pv, ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_plan.restype = ci
-        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ci, ci, ci, pv, vp, vp]
+        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, ci, pv, vp, vp]
         L.sawattn_mfma_probe.restype = ci
         L.sawattn_mfma_probe.argtypes = [vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
         L.sawattn_last_error.restype = ctypes.c_char_p
@@ -108,22 +109,27 @@ def _in_dtype_code(dtype) -> int:
     return {"f16": F16, "bf16": BF16}.get(dtype, _DTYPE_CODE.get(dtype, dtype))
 
 
+def _scale_or_usual(scale, d: int) -> float:
+    return float(scale) if scale is not None else 1.0 / math.sqrt(d)
+
+
 def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False, variant: Variant = None,
-                         dtype="f16") -> dict:
+                         dtype="f16", scale: float = None) -> dict:
+    """`scale` = None stands for the usual 1/sqrt(d)."""
     info = LaunchInfo()
-    _check(lib().attn_fwd_launch_info(B, H, N, d, int(bool(causal)), _in_dtype_code(dtype), _vptr(variant),
-                                      ctypes.byref(info)))
+    _check(lib().attn_fwd_launch_info(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _in_dtype_code(dtype),
+                                      _vptr(variant), ctypes.byref(info)))
     return info.as_dict()
 
 
 def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_order="sawtooth",
-                  variant: Variant = None, dtype="f16"):
+                  variant: Variant = None, dtype="f16", scale: float = None):
     """Host-side schedule: returns (trace[grid, max_local, 4], count[grid]) as CPU int32 tensors."""
-    info = attn_fwd_launch_info(B, H, N, d, causal, variant, dtype)
+    info = attn_fwd_launch_info(B, H, N, d, causal, variant, dtype, scale)
     trace = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32)
     count = torch.zeros((info["grid"],), dtype=torch.int32)
-    _check(lib().attn_fwd_plan(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order], _in_dtype_code(dtype),
-                               _vptr(variant), trace.data_ptr(), count.data_ptr()))
+    _check(lib().attn_fwd_plan(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _SCAN_CODE[scan_order],
+                               _in_dtype_code(dtype), _vptr(variant), trace.data_ptr(), count.data_ptr()))
     return trace, count
 
 
@@ -171,7 +177,7 @@ def attn_fwd_variant(Q, K, V, O=None, *, scale: float, causal: bool = False, sca
     B, H, N, d = Q.shape
     tr = cnt = None
     if trace:
-        info = attn_fwd_launch_info(B, H, N, d, causal, variant, Q.dtype)
+        info = attn_fwd_launch_info(B, H, N, d, causal, variant, Q.dtype, scale)
         tr = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32,
                         device=Q.device)
         cnt = torch.zeros((info["grid"],), dtype=torch.int32, device=Q.device)

@@ -50,6 +50,7 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef unsigned u4 __attribute__((ext_vector_type(4)));
+typedef unsigned u16v __attribute__((ext_vector_type(16)));
 typedef unsigned u2 __attribute__((ext_vector_type(2)));
 typedef short s4 __attribute__((ext_vector_type(4)));
 typedef short s8 __attribute__((ext_vector_type(8)));
@@ -302,6 +303,10 @@ template <bool BF16>
 __device__ __forceinline__ void mfma_s(f16v& acc, u4 k_frag, const u4& q_frag) {
     if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
     else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
+}
+// First MFMA of an S^T block whose accumulator starts from the register block `init`.
+__device__ __forceinline__ void mfma_s_init(f16v& acc, u4 k_frag, const u4& q_frag, const f16v& init) {
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3" : "=&v"(acc) : "v"(k_frag), "a"(q_frag), "v"(init));
 }
 __device__ __forceinline__ void mfma_o(f16v& acc, s8 v_frag, const u4& p_frag) {
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_frag), "v"(p_frag));
@@ -776,18 +781,31 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
 }
 
 // ------------------------------------------------------------------------------------------------
-// Wide variant (head dimension 128): a wavefront owns 64 query rows as two 32-row halves, a workgroup
-// 256 rows, one workgroup per CU.  Every K and V^T fragment read from LDS feeds two MFMAs, one per
-// half, which halves the LDS operand traffic and the L2 -> LDS traffic per flop; the chip being
-// power limited, that is where the remaining throughput is.  With one wavefront per SIMD there is
-// no second wavefront to hide latencies behind, so K and V are fetched three tiles ahead into four
-// LDS buffers each and a fetch has two whole iterations to land.
+// Wide variant (head dimension 128, binary16 inputs): a wavefront owns 64 query rows as two 32-row
+// halves, a workgroup 256 rows, one workgroup per CU.  Every K and V^T fragment read from LDS feeds
+// two MFMAs, one per half, which halves the LDS operand traffic and the L2 -> LDS traffic per flop.
+//
+// With one wavefront per SIMD the instruction stream of that wavefront is all the SIMD has: an MFMA
+// occupies the matrix pipe for 32 cycles, and whatever the wavefront issues between two MFMAs
+// (about 5 cycles per vector instruction, 9 per exponential) has to fit under those 32 cycles or the
+// pipe idles.  So the vector work per score is cut to the exponential, half a convert, half a
+// maximum and the row sum, and spread evenly over the MFMAs:
+//   * Q is multiplied by scale*log2(e) once, when the query tile is loaded, and the first MFMA of
+//     every S^T block starts from an accumulator block that holds -M (the reference maximum of the
+//     lane's query row) instead of zero, so the MFMAs deliver score - M directly;
+//   * S^T is computed block by block (kv rows 0..31 of the tile, then 32..63): the exponentials of
+//     the second block of tile i run under the first-block MFMAs of S(i+1)^T, which do not touch it,
+//     the row sums of tile i under the second-block MFMAs; under the MFMAs of O^T += V(i)^T P(i)^T
+//     come the maxima of S(i+1) and the exponentials of its first block, which go into the operand
+//     registers of P as the second product releases them.  Those exponentials are taken before the
+//     maxima are all known; when a maximum exceeds the slack they are redone (rarely).
+// K and V are fetched three and two tiles ahead into four LDS buffers each, so that a fetch has two
+// whole iterations to land.
 constexpr int kWideBuffers = 4;
 constexpr int kWideLdsBytes = 2 * kWideBuffers * Geo<128>::kTile;
 
-template <bool BF16>
 __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], const LaneMap<128>& lm, const char* Kh,
-                                                     const char* Vh, float c, int j_first, int step, int count, int lane,
+                                                     const char* Vh, int j_first, int step, int count, int lane,
                                                      LDS_PTR(char) lds) {
     constexpr int D = 128;
     using G = Geo<D>;
@@ -800,12 +818,11 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
     float L_hi[2] = {0.f, 0.f};   // second partials of the running sums, folded into st[h].L
-    f16v A[2][2];       // [half][block]: S^T of the tile one ahead
-    float x[2][32];     // [half]: score*c - M of the current tile
-    u4 pf[2][4];        // [half]: its probabilities as B operands
-    u4 vreg[NL];        // bfloat16 V chunks in flight (BF16 only)
+    f16v S[2][2];                 // [half][block]: score - M; pair u = 0..15 of a half is S[h][u / 8][2 * (u % 8) .. + 1]
+    f16v negM[2];                 // [half]: -M in all 16 registers, the initial accumulator of an S^T block
+    u4 pf[2][4];                  // [half][contraction step]: probabilities as B operands; pair u is pf[h][u / 4][u % 4]
     float e0[2][16], e1[2][16];
-    float tmax_ahead[2] = {0.f, 0.f};
+    float tmax_ahead[2] = {0.f, 0.f};   // this lane's maximum of the tile one ahead, relative to M
     mfma_guard(st[0].o);
     mfma_guard(st[1].o);
 
@@ -817,52 +834,40 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     };
     auto fetch_k = [&](int i, int l) { load_to_lds_16B(tile_base(Kh, i), lm.fill_src[l], lds0 + (i & 3) * G::kTile + lm.fill_dst + l * 4096); };
     auto fetch_v = [&](int i, int l) { load_to_lds_16B(tile_base(Vh, i), lm.fill_src[l], lds0 + VB + (i & 3) * G::kTile + lm.fill_dst + l * 4096); };
-    auto v_to_regs = [&](int i, int l) { vreg[l] = *reinterpret_cast<const u4*>(tile_base(Vh, i) + lm.fill_src[l]); };
     // LDS read addresses of this lane: K of the tile one ahead (buffer 1 at the start), V of the current tile
     unsigned rk[KS], rv[DB][2];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) rk[ks] = lds0 + G::kTile + lm.k_rd[ks];
 #pragma unroll
     for (int db = 0; db < DB; ++db) { rv[db][0] = lds0 + VB + lm.v_rd[db][0]; rv[db][1] = lds0 + VB + lm.v_rd[db][1]; }
-    auto k_read = [&](int m) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[m / 2] + (m & 1) * 32 * G::kRowBytes); };
+    // K fragment (ks, b): contraction step ks, kv rows 32b .. 32b+31
+    auto k_read = [&](int ks, int b) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[ks] + b * 32 * G::kRowBytes); };
     auto v_read = [&](int idx) -> s8 {
         const int ks = idx / DB, db = idx % DB;
         const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][0] + ks * 16 * G::kRowBytes));
         const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s4))(size_t)(rv[db][1] + ks * 16 * G::kRowBytes));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
-    auto rescale = [&](int h, float tmax) {
-        st[h].L += L_hi[h];
-        L_hi[h] = 0.f;
-        const float Mnew = fmaxf(st[h].M, tmax);
-        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st[h].M - Mnew);
-        st[h].M = Mnew;
-        st[h].L *= alpha;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
+    // Softmax work items of half h, pair u = 0..15: the two exponentials, the convert into the B operand,
+    // the addition to the running sum.
+    auto exp2_pair = [&](int h, int u) {
+        e0[h][u] = fast_exp2(S[h][u / 8][2 * (u % 8)]);
+        e1[h][u] = fast_exp2(S[h][u / 8][2 * (u % 8) + 1]);
     };
-    // exp unit u (0..16) of half h: the two exponentials of pair u, and the convert + sum of pair u-1
-    // (with one wavefront per SIMD nothing hides the latency between dependent vector instructions, so the
-    // convert comes first and the sum that needs its result last)
-    auto exp_unit = [&](int h, int u) {
-        h2 ph;
-        if (u >= 1 && u <= 16) {
-            ph = __builtin_convertvector(f2{e0[h][u - 1], e1[h][u - 1]}, h2);
-            pf[h][(u - 1) / 4][(u - 1) % 4] = __builtin_bit_cast(unsigned, ph);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (u < 16) {
-            e0[h][u] = fast_exp2(x[h][2 * u]);
-            e1[h][u] = fast_exp2(x[h][2 * u + 1]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (u >= 1 && u <= 16) add_pair(st[h].L, L_hi[h], ph);
+    auto convert_pair = [&](int h, int u) {
+        pf[h][u / 4][u % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{e0[h][u], e1[h][u]}, h2));
     };
-    auto shifted_scores = [&](int h) {
+    auto sum_pair = [&](int h, int u) {
+        const unsigned word = pf[h][u / 4][u % 4];   // (a copy: bit casts of a vector element do not read that element)
+        add_pair(st[h].L, L_hi[h], __builtin_bit_cast(h2, word));
+    };
+    auto first_block_probabilities = [&](int h) {
 #pragma unroll
-        for (int r = 0; r < 32; ++r) x[h][r] = __builtin_fmaf(A[h][r >> 4][r & 15], c, -st[h].M);
+        for (int u = 0; u < 8; ++u) { exp2_pair(h, u); convert_pair(h, u); }
+    };
+    auto set_negM = [&](int h) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) negM[h][r] = -st[h].M;
     };
 
     // ---------------------------------------------------------------- prologue: K(0..2), V(0..1) on their way, S(0)
@@ -871,106 +876,125 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 #pragma unroll
         for (int l = 0; l < NL; ++l) fetch_k(i, l);
         if (i < 2) {
-            if constexpr (BF16) {
 #pragma unroll
-                for (int l = 0; l < NL; ++l) v_to_regs(i, l);
-                regs_to_lds_f16<D>(vreg, lm, lane, lds + VB + i * G::kTile);
-            } else {
-#pragma unroll
-                for (int l = 0; l < NL; ++l) fetch_v(i, l);
-            }
+            for (int l = 0; l < NL; ++l) fetch_v(i, l);
         }
     }
     wait_tile_landed();
     __syncthreads();
     u4 ak[RA];          // the first K fragments of the tile one ahead, read before the iteration starts
     {
-        u4 a[NA];
+        u4 a[NA];       // a[m]: fragment (ks, b) = (m / 2, m % 2) of tile 0 (buffer 0)
+        auto k0_read = [&](int m) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[m / 2] - G::kTile + (m & 1) * 32 * G::kRowBytes); };
 #pragma unroll
-        for (int m = 0; m < RA; ++m) a[m] = *(LDS_PTR(u4))(size_t)(rk[m / 2] - G::kTile + (m & 1) * 32 * G::kRowBytes);
+        for (int m = 0; m < RA; ++m) a[m] = k0_read(m);
 #pragma unroll
         for (int m = 0; m < NA; ++m) {
-            if (m + RA < NA) a[m + RA] = *(LDS_PTR(u4))(size_t)(rk[(m + RA) / 2] - G::kTile + ((m + RA) & 1) * 32 * G::kRowBytes);
+            if (m + RA < NA) a[m + RA] = k0_read(m + RA);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
-                else mfma_s<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
+                if (m < 2) mfma_s_first<false>(S[h][m & 1], a[m], st[h].qf[m / 2]);
+                else mfma_s<false>(S[h][m & 1], a[m], st[h].qf[m / 2]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int m = 0; m < RA; ++m) ak[m] = k_read(m);
-        mfma_settle_v(A[0][0], A[0][1], A[1][0], A[1][1]);
+        ak[0] = k_read(0, 0);
+        ak[1] = k_read(1, 0);
+        mfma_settle_v(S[0][0], S[0][1], S[1][0], S[1][1]);
+        mfma_settle_a(st[0].o);
+        mfma_settle_a(st[1].o);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            float mx = fmaxf(A[h][0][0], A[h][0][1]);
+            float mx = fmaxf(S[h][0][0], S[h][0][1]);
 #pragma unroll
-            for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, A[h][r >> 4][r & 15]), A[h][r >> 4][(r & 15) + 1]);
-            const float tmax = pair_max(mx) * c;
-            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + kRescaleSlack)) != 0) rescale(h, tmax);
-            shifted_scores(h);
+            for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, S[h][r >> 4][r & 15]), S[h][r >> 4][(r & 15) + 1]);
+            const float tmax = pair_max(mx);
+            // the first tile of a query tile finds M = -inf and takes its own maximum as the reference
+            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + kRescaleSlack)) != 0) {
+                st[h].L += L_hi[h];
+                L_hi[h] = 0.f;
+                const float Mnew = fmaxf(st[h].M, tmax);
+                const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st[h].M - Mnew);
+                st[h].M = Mnew;
+                st[h].L *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
+            }
+#pragma unroll
+            for (int r = 0; r < 32; ++r) S[h][r >> 4][r & 15] -= st[h].M;
+            set_negM(h);
+            first_block_probabilities(h);
         }
         mfma_guard(st[0].o);
         mfma_guard(st[1].o);
     }
 
     // ---------------------------------------------------------------- steady state: iteration i
-    // computes S(i+1) from K buffer (i+1)&3 and adds V(i)^T P(i)^T from V buffer i&3; fetches K(i+3) and V(i+2).
+    // enters with the scores of tile i in S and the probabilities of its first block in pf[.][0..1];
+    // computes S(i+1)^T from K buffer (i+1)&3 and adds V(i)^T P(i)^T from V buffer i&3; fetches K(i+3) and V(i+2).
     // Its barrier sits in the middle of the second product: by then everything fetched before this
     // iteration (K(i+2), V(i+1) among it) has landed, so the first fragments of the next iteration can be read
     // before this one ends, and the buffers this iteration's fetches overwrite (of K(i-1), V(i-2)) were last
     // read before the previous barrier.  Returns whether a reference maximum has to be raised before
     // tile i+1 can be used.
     auto iteration = [&](int i) -> bool {
-        const unsigned vdst = lds0 + VB + ((i + 2) & 3) * G::kTile + lm.fill_dst;
         // this iteration's fetches: K(i+3) and V(i+2), source tile bases and LDS destinations of this wavefront
         const char* kbase = tile_base(Kh, i + 3);
         const char* vbase = tile_base(Vh, i + 2);
         const unsigned kdst_s = __builtin_amdgcn_readfirstlane(lds0 + ((i + 3) & 3) * G::kTile + lm.fill_dst);
-        const unsigned vdst_s = __builtin_amdgcn_readfirstlane(vdst);
+        const unsigned vdst_s = __builtin_amdgcn_readfirstlane(lds0 + VB + ((i + 2) & 3) * G::kTile + lm.fill_dst);
         s8 av[NB];
-        // ---- phase A: S(i+1)^T for both halves, exponentials of tile i in between
+        // ---- phase A: S(i+1)^T, block 0 (kv rows 0..31) for both halves, then block 1.
+        //      Slot t = 0..31 is the t-th MFMA; fragment n = t / 2 of the block-major order is (ks, b) = (n % 8, n / 8).
         {
-            u4 a[NA];
-#pragma unroll
-            for (int m = 0; m < RA; ++m) a[m] = ak[m];
+            u4 a[NA];   // indexed by n
+            a[0] = ak[0];
+            a[1] = ak[1];
             auto constexpr_fetch = [&](int li) {
-                if (li < NL) {
-                    if (li == 0) load_to_lds_16B_at<0>(kbase, lm.fill_src[0], kdst_s);
-                    if (li == 1) load_to_lds_16B_at<4096>(kbase, lm.fill_src[1], kdst_s);
-                    if (li == 2) load_to_lds_16B_at<8192>(kbase, lm.fill_src[2], kdst_s);
-                    if (li == 3) load_to_lds_16B_at<12288>(kbase, lm.fill_src[3], kdst_s);
-                } else if constexpr (BF16) {
-                    vreg[li - NL] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[li - NL]);
-                } else {
-                    if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
-                    if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
-                    if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
-                    if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
-                }
+                if (li == 0) load_to_lds_16B_at<0>(kbase, lm.fill_src[0], kdst_s);
+                if (li == 1) load_to_lds_16B_at<4096>(kbase, lm.fill_src[1], kdst_s);
+                if (li == 2) load_to_lds_16B_at<8192>(kbase, lm.fill_src[2], kdst_s);
+                if (li == 3) load_to_lds_16B_at<12288>(kbase, lm.fill_src[3], kdst_s);
+                if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
+                if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
+                if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
+                if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
             };
             // Fragments are read from LDS two at a time, one pair ahead, and used in the order second, first:
             // the one wait for the later read covers both (half as many waits in the instruction stream).
 #pragma unroll
             for (int q = 0; q < NA; ++q) {
                 if ((q & 1) == 0) {
-                    if (q + 2 < NA) { a[q + 2] = k_read(q + 2); a[q + 3] = k_read(q + 3); }
+                    if (q + 2 < NA) { a[q + 2] = k_read((q + 2) % 8, (q + 2) / 8); a[q + 3] = k_read((q + 3) % 8, (q + 3) / 8); }
                     else { av[0] = v_read(0); av[1] = v_read(1); }   // the first V^T fragments of the second product
                 }
-                const int m = q ^ 1;
+                const int n = q ^ 1, ks = n % 8, b = n / 8;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    if (m < 2) mfma_s_first<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
-                    else mfma_s<BF16>(A[h][m & 1], a[m], st[h].qf[m / 2]);
-                    exp_unit(h, q);
-                    if (h == 0 && (q & 1) == 0) {
-                        constexpr_fetch(q / 2);      // 8 loads over 16 fragments
+                    const int t = 2 * q + h;
+                    if (q % 8 == 0) mfma_s_init(S[h][b], a[n], st[h].qf[ks], negM[h]);   // the block's first MFMA
+                    else mfma_s<false>(S[h][b], a[n], st[h].qf[ks]);
+                    if (t < 16) {
+                        // exponentials of the second block of tile i: pair 8 + t/2 of half t%2, convert of the one before
+                        const int hh = t & 1, u = 8 + t / 2;
+                        if (u > 8) convert_pair(hh, u - 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                        exp2_pair(hh, u);
+                    } else {
+                        if (t == 16) convert_pair(0, 15);
+                        if (t == 17) convert_pair(1, 15);
+                        __builtin_amdgcn_sched_barrier(0);
+                        // row sums of tile i: words 2(t-16), 2(t-16)+1 of the 32
+                        const int w0 = 2 * (t - 16);
+                        sum_pair(w0 & 1, w0 >> 1);
+                        sum_pair((w0 + 1) & 1, (w0 + 1) >> 1);
                     }
+                    if (h == 0 && (q & 1) == 0) constexpr_fetch(q / 2);      // 8 loads over 16 fragments
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            exp_unit(0, 16);
-            exp_unit(1, 16);
         }
         // K read addresses move on to tile i+2
         {
@@ -978,74 +1002,56 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) rk[ks] += dk;
         }
-        // ---- phase B, first half: row maxima of A and the rescale check
+        // ---- phase B: O^T += V(i)^T P(i)^T.  Under its MFMAs (slot t = 0..31): the row maxima of S(i+1) and
+        //      their check against the slack (slots 2..9), then the first-block exponentials of tile i+1, whose
+        //      converts overwrite pf[.][0] (free after slot 7) and pf[.][1] (free after slot 15).
         float mx[2] = {0.f, 0.f};
-        constexpr int HB = NB / 2;         // fragments before the check
-        constexpr int MS = 1;              // first fragment whose slots may read A (MFMA result latency)
-        constexpr int MPS = (16 + (HB - MS) - 1) / (HB - MS);   // max3 ops per slot and half
-        // (the two halves' maxima are separate dependency chains; their steps alternate)
+        bool need = false;
 #pragma unroll
-        for (int idx = 0; idx < HB; ++idx) {
-            if ((idx & 1) == 0) { av[idx + 2] = v_read(idx + 2); av[idx + 3] = v_read(idx + 3); }
-            const int f = idx ^ 1;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                mfma_o(st[h].o[f % DB], av[f], pf[h][f / DB]);
-                if (idx >= MS) {
-#pragma unroll
-                    for (int q = 0; q < MPS; ++q) {
-                        const int step2 = ((idx - MS) * 2 + h) * MPS + q;   // step of the alternating sequence
-                        const int hh = step2 & 1, op = step2 >> 1;          // op-th max3 of half hh: elements 2*op, 2*op+1
-                        if (op < 16) {
-                            const float u0 = A[hh][(2 * op) >> 4][(2 * op) & 15], u1 = A[hh][(2 * op) >> 4][((2 * op) & 15) + 1];
-                            mx[hh] = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx[hh], u0), u1);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
+        for (int idx = 0; idx < NB; ++idx) {
+            if (idx == NB / 2) {
+                // ---- everything fetched before this iteration has landed; publish it
+                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                __syncthreads();
             }
-        }
-        tmax_ahead[0] = pair_max(mx[0]) * c;
-        tmax_ahead[1] = pair_max(mx[1]) * c;
-        const bool need = __builtin_amdgcn_ballot_w64(!(tmax_ahead[0] <= st[0].M + kRescaleSlack) ||
-                                                      !(tmax_ahead[1] <= st[1].M + kRescaleSlack)) != 0;
-        // ---- everything fetched before this iteration has landed; publish it
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        __syncthreads();
-        // ---- phase B, second half, with the shifted scores of tile i+1 in between (and, for
-        //      bfloat16, the conversion of the fetched V chunks)
-        constexpr int FPS = 32 / (NB - HB);                        // fmas per slot and half
-        constexpr int CPS = (NL * 4 + 2 * (NB - HB) - 1) / (2 * (NB - HB));   // bf16 pair conversions per slot
-#pragma unroll
-        for (int idx = HB; idx < NB; ++idx) {
             if ((idx & 1) == 0) {
                 if (idx + 2 < NB) { av[idx + 2] = v_read(idx + 2); av[idx + 3] = v_read(idx + 3); }
-                else { ak[0] = k_read(0); ak[1] = k_read(1); }   // the first K fragments of the next iteration
+                else { ak[0] = k_read(0, 0); ak[1] = k_read(1, 0); }   // the first K fragments of the next iteration
             }
             const int f = idx ^ 1;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
+                const int t = 2 * idx + h;
                 mfma_o(st[h].o[f % DB], av[f], pf[h][f / DB]);
+                if (t >= 2 && t < 10) {
+                    // four maxima per slot, the two halves' chains alternating
 #pragma unroll
-                for (int q = 0; q < FPS; ++q) {
-                    const int r = (idx - HB) * FPS + q;
-                    x[h][r] = __builtin_fmaf(A[h][r >> 4][r & 15], c, -st[h].M);
-                }
-                if constexpr (BF16) {
-#pragma unroll
-                    for (int q = 0; q < CPS; ++q) {
-                        const int w = ((idx - HB) * 2 + h) * CPS + q;    // w-th 32-bit word of the fetched chunks
-                        if (w < NL * 4) {
-                            f2 y;
-                            y[0] = __builtin_bit_cast(float, vreg[w / 4][w % 4] << 16);
-                            y[1] = __builtin_bit_cast(float, vreg[w / 4][w % 4] & 0xffff0000u);
-                            vreg[w / 4][w % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(y, h2));
-                            if (w % 4 == 3)
-                                *(LDS_PTR(u4))(size_t)(vdst + (w / 4) * 4096 + lane * 16) = vreg[w / 4];
-                        }
+                    for (int q = 0; q < 4; ++q) {
+                        const int n = (t - 2) * 4 + q, hh = n & 1, op = n >> 1;    // op-th max3 of half hh
+                        const float u0 = S[hh][(2 * op) >> 4][(2 * op) & 15], u1 = S[hh][(2 * op) >> 4][((2 * op) & 15) + 1];
+                        mx[hh] = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx[hh], u0), u1);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+                if (t == 10) {
+                    tmax_ahead[0] = mx[0];
+                    tmax_ahead[1] = mx[1];
+                    need = __builtin_amdgcn_ballot_w64(!(mx[0] <= kRescaleSlack) || !(mx[1] <= kRescaleSlack)) != 0;
+                }
+                if (t >= 10 && t < 18) {            // pairs 0..3 of both halves: pf[.][0]
+                    const int hh = t & 1, u = (t - 10) / 2;
+                    if (u > 0) convert_pair(hh, u - 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    exp2_pair(hh, u);
+                }
+                if (t >= 18 && t < 26) {            // pairs 4..7: pf[.][1]
+                    const int hh = t & 1, u = 4 + (t - 18) / 2;
+                    convert_pair(hh, u - 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    exp2_pair(hh, u);
+                }
+                if (t == 26) convert_pair(0, 7);
+                if (t == 27) convert_pair(1, 7);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -1057,8 +1063,11 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         }
         return need;
     };
+    // Between two iterations: the scores of the coming tile exceed the slack somewhere.  The reference maximum
+    // of that half goes up (per query row), the sum and the accumulators follow, the scores are taken relative
+    // to it and the first-block probabilities are redone.
     auto raise_reference = [&]() {
-        mfma_settle_v(A[0][0], A[0][1], A[1][0], A[1][1]);
+        mfma_settle_v(S[0][0], S[0][1], S[1][0], S[1][1]);
         mfma_settle_a(st[0].o);
         mfma_settle_a(st[1].o);
 #pragma unroll
@@ -1067,13 +1076,26 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             // would carry both halves' results along as lane masks)
             float t = tmax_ahead[h];
             asm volatile("" : "+v"(t));
-            if (__builtin_amdgcn_ballot_w64(!(t <= st[h].M + kRescaleSlack)) != 0) {
-                rescale(h, t);
-                shifted_scores(h);
+            t = pair_max(t);     // the two lanes of a query row move together
+            if (__builtin_amdgcn_ballot_w64(!(t <= kRescaleSlack)) != 0) {
+                const float up = fmaxf(t, 0.f);
+                const float alpha = fast_exp2(-up);
+                st[h].M += up;
+                st[h].L = (st[h].L + L_hi[h]) * alpha;
+                L_hi[h] = 0.f;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
+#pragma unroll
+                for (int r = 0; r < 32; ++r) S[h][r >> 4][r & 15] -= up;
+                set_negM(h);
+                first_block_probabilities(h);
             }
         }
         mfma_guard(st[0].o);
         mfma_guard(st[1].o);
+        asm volatile("s_nop 3" : "+v"(negM[0]), "+v"(negM[1]));   // written by vector instructions, read by the next MFMAs
     };
     int i = 0;
     while (i + 1 < count) {
@@ -1086,9 +1108,15 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         if (need) raise_reference();
     }
 
-    // ---------------------------------------------------------------- last tile: probabilities, then O^T += V^T P^T
+    // ---------------------------------------------------------------- last tile: the rest of its probabilities, then O^T += V^T P^T
+    mfma_settle_v(S[0][0], S[0][1], S[1][0], S[1][1]);
 #pragma unroll
-    for (int u = 0; u <= 16; ++u) { exp_unit(0, u); exp_unit(1, u); }
+    for (int u = 8; u < 16; ++u) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) { exp2_pair(h, u); convert_pair(h, u); }
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) { sum_pair(0, u); sum_pair(1, u); }
     {
         s8 av[NB];
 #pragma unroll
@@ -1138,8 +1166,18 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         for (int ks = 0; ks < KS; ++ks) {
             u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
             v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
-            if constexpr (NH == 2) asm volatile("" : "=a"(st[h].qf[ks]) : "0"(v));   // accumulation registers from here on
-            else st[h].qf[ks] = v;
+            if constexpr (NH == 2) {
+                // the wide variant folds scale*log2(e) into Q (one rounding to binary16 per element)
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const unsigned word = v[w];   // (a copy: bit casts of a vector element do not read that element)
+                    const f2 x = __builtin_convertvector(__builtin_bit_cast(h2, word), f2) * p.c;
+                    v[w] = __builtin_bit_cast(unsigned, __builtin_convertvector(x, h2));
+                }
+                asm volatile("" : "=a"(st[h].qf[ks]) : "0"(v));   // accumulation registers from here on
+            } else {
+                st[h].qf[ks] = v;
+            }
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db)
@@ -1148,7 +1186,7 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         st[h].M = -INFINITY;
         st[h].L = 0.f;
     }
-    const float c = p.c;
+    const float c = NH == 2 ? 1.0f : p.c;   // (the wide variant's Q carries the factor)
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
     // the tiles that reach past the first row of this query tile.  They sit at one end of the scan,
@@ -1157,12 +1195,27 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
     const int jm = CAUSAL ? (t * TQ) / kTileKV : ((N % kTileKV) ? kv_tiles - 1 : kv_tiles);
     const int n_masked = nkv > jm ? nkv - jm : 0;
     const int n_plain = nkv - n_masked;
+    // (The wide variant has no registers to spare: each of its runs builds the per-lane address tables afresh,
+    // from a lane index the compiler cannot see through, so that none of them stays live across the other run.)
     auto plain = [&](int j_first) {
-        if constexpr (NH == 1) pipelined_range<D, BF16>(st[0], lm, Kh, Vh, c, j_first, step, n_plain, lane, lds);
-        else pipelined_range_wide<BF16>(st, lm, Kh, Vh, c, j_first, step, n_plain, lane, lds);
+        if constexpr (NH == 1) {
+            pipelined_range<D, BF16>(st[0], lm, Kh, Vh, c, j_first, step, n_plain, lane, lds);
+        } else {
+            int l2 = lane;
+            asm volatile("" : "+v"(l2));
+            const LaneMap<D> lm2(wave, l2);
+            pipelined_range_wide(st, lm2, Kh, Vh, j_first, step, n_plain, l2, lds);
+        }
     };
     auto masked = [&](int j_first) {
-        general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, lane, lds);
+        if constexpr (NH == 1) {
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, lane, lds);
+        } else {
+            int l2 = lane;
+            asm volatile("" : "+v"(l2));
+            const LaneMap<D> lm2(wave, l2);
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm2, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, l2, lds);
+        }
     };
     if (step > 0) {
         plain(j0);
@@ -1392,7 +1445,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 }
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
-int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out) {
+int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, float scale, const sawattn_variant* v, Schedule* out) {
     int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
@@ -1401,10 +1454,10 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.decode must be SAWATTN_DECODE_DOMAIN or SAWATTN_DECODE_LINEAR");
         if (v->rows_per_wavefront != 0 && v->rows_per_wavefront != 32 && v->rows_per_wavefront != 64)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.rows_per_wavefront must be 0 (default), 32 or 64");
-        if (v->rows_per_wavefront == 64 && d != 128)
-            return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
+        if (v->rows_per_wavefront == 64 && (d != 128 || bf16))
+            return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128 and binary16 inputs");
         rows = v->rows_per_wavefront;
-        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16);
+        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16, scale);
         if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : kTileQ))
             return fail(SAWATTN_ERR_INVALID_ARG,
                         "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per wavefront)");
@@ -1415,7 +1468,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
     }
-    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
+    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16, scale);
     const int tile_q = rows == 64 ? 2 * kTileQ : kTileQ;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q);
@@ -1440,7 +1493,7 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     if ((trace == nullptr) != (trace_count == nullptr))
         return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be given together");
     Schedule sched;
-    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &sched);
+    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &sched);
     if (rc != SAWATTN_OK) return rc;
     {   // A workgroup writes its O rows while others still read Q, K, V: O may not share memory with them.
         const unsigned long long elems = (unsigned long long)B * H * N * d;
@@ -1466,7 +1519,6 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool bf = in_dtype == SAWATTN_BF16, ca = causal != 0;
     if (sched.tile_q > kTileQ) {
-        if (bf) return ca ? launch<128, true, true, 2>(p, grid, stream) : launch<128, true, false, 2>(p, grid, stream);
         return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
     if (d == 128) {
@@ -1494,24 +1546,26 @@ int attn_fwd_variant(const void* Q, const void* K, const void* V, void* O, int B
                         trace_count);
 }
 
-int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,
-                         sawattn_launch_info* out) {
+int attn_fwd_launch_info(int B, int H, int N, int d, float scale, int causal, int in_dtype,
+                         const sawattn_variant* variant, sawattn_launch_info* out) {
     if (!out) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "out must be non-null");
+    if (!std::isfinite(scale)) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "scale must be finite");
     if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
         return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
     int rc = sawattn::check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     sawattn::Schedule s;
-    rc = sawattn::schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
+    rc = sawattn::schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     sawattn::fill_info(s, d, out);
     return SAWATTN_OK;
 }
 
-int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in_dtype, const sawattn_variant* variant,
-                  int32_t* trace, int32_t* trace_count) {
+int attn_fwd_plan(int B, int H, int N, int d, float scale, int causal, int scan_order, int in_dtype,
+                  const sawattn_variant* variant, int32_t* trace, int32_t* trace_count) {
     using namespace sawattn;
     if (!trace || !trace_count) return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be non-null");
+    if (!std::isfinite(scale)) return fail(SAWATTN_ERR_INVALID_ARG, "scale must be finite");
     if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
         return fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
     if (scan_order != SAWATTN_SCAN_CYCLIC && scan_order != SAWATTN_SCAN_SAWTOOTH)
@@ -1519,7 +1573,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     Schedule s;
-    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
+    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     // the kernel's outer loop, one workgroup at a time
     for (int wg = 0; wg < s.grid; ++wg) {

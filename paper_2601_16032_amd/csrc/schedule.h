@@ -44,11 +44,12 @@ SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b);
 // Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
 // workgroup tiles) for head dimension 128 and binary16 inputs once the steady state dominates, i.e.
 // every resident workgroup of a domain gets at least two full-length tiles of a head (four under the
-// causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured: +3.5 to
-// +4.5 % there; with bfloat16 inputs the V conversion makes the wide variant's single instruction
-// stream longer and it only pays from about 64K keys on.)
-SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16) {
-    if (d != 128 || bf16) return 32;
+// causal mask, where a tile walks half the keys on average); 32 rows otherwise.  The wide variant
+// rounds scale*log2(e)*Q to binary16, which costs accuracy in proportion to the size of the scores;
+// it is therefore only chosen for |scale| <= 2/sqrt(d), twice the usual softmax scale.
+SAW_HD bool wide_scale_ok(float scale, int d) { return scale * scale * (float)d <= 4.0f; }
+SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16, float scale) {
+    if (d != 128 || bf16 || !wide_scale_ok(scale, d)) return 32;
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
     return (wide_tiles + parts - 1) / parts >= (causal ? 128 : 64) ? 64 : 32;

@@ -1,6 +1,7 @@
 """CPU-only tests of the host side: the C ABI surface, argument validation, the work decode /
 scan-direction schedule against its oracle, and the traffic model against the paper's counters."""
 import ctypes
+import math
 import os
 import re
 
@@ -242,6 +243,9 @@ def test_variant_fields_are_validated(sa):
     with pytest.raises(binding.SawattnError) as e:
         sa.attn_fwd_launch_info(1, 8, 2048, 64, False, sa.variant(rows_per_wavefront=64))
     assert e.value.code == binding.ERR_UNSUPPORTED
+    with pytest.raises(binding.SawattnError) as e:     # 64 rows per wavefront: binary16 inputs only
+        sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64), dtype="bf16")
+    assert e.value.code == binding.ERR_UNSUPPORTED
     with pytest.raises(binding.SawattnError):
         sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64, slots_per_domain=33))
     with pytest.raises(binding.SawattnError):
@@ -249,6 +253,26 @@ def test_variant_fields_are_validated(sa):
     assert sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=96))["slots"] == 96
     with pytest.raises(binding.SawattnError):
         sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=97))
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_default_rows_per_wavefront_depends_on_dtype_length_and_scale(sa, causal):
+    """64 rows per wavefront is the default only where it is both faster and as accurate: d = 128, binary16
+    inputs, long sequences, |scale| <= 2/sqrt(d) (it rounds scale*log2(e)*Q to binary16)."""
+    H, d = 8, 128
+    N = 256 * (128 if causal else 64)
+    usual = 1.0 / math.sqrt(d)
+    for dtype, n, scale, rows in (("f16", N, None, 64), ("f16", N, usual, 64), ("f16", N, -2.0 * usual, 64),
+                                  ("f16", N, 2.01 * usual, 32), ("f16", N, 1.0, 32), ("bf16", N, None, 32),
+                                  ("f16", N - 256, None, 32)):
+        info = sa.attn_fwd_launch_info(1, H, n, d, causal, dtype=dtype, scale=scale)
+        geo = so.launch_geometry(1, H, n, d=d, causal=causal, dtype=dtype, scale=scale)
+        assert info["tile_q"] == geo["tile_q"] == 4 * rows, (dtype, n, scale)
+        assert info["grid"] == geo["grid"]
+    assert sa.attn_fwd_launch_info(1, H, N, 64, causal)["tile_q"] == 128
+    with pytest.raises(binding.SawattnError) as e:
+        sa.attn_fwd_launch_info(1, H, N, d, causal, scale=float("inf"))
+    assert e.value.code == binding.ERR_INVALID_ARG
 
 
 # ------------------------------------------------------------------ traffic model vs the paper's counters
