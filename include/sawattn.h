@@ -105,8 +105,8 @@ typedef struct sawattn_variant {
                                 grows with the size of the scores; UNSUPPORTED for bfloat16 inputs);
                                 0 = default: 64 for d = 128, binary16 inputs, |scale| <= 2/sqrt(d),
                                 slots_per_domain <= 32 and sequences long enough that every workgroup of an
-                                XCD gets at least two 256-row tiles of a head (four under the causal mask):
-                                ceil(ceil(N/256) / parts_per_head) >= 64 (128); else 32. */
+                                XCD gets at least one 256-row tile of a head (two under the causal mask):
+                                ceil(ceil(N/256) / parts_per_head) >= 32 (64); else 32. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round

@@ -53,12 +53,12 @@ def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0
                            dtype: str = "f16", scale: float = None) -> int:
     """The library's choice when the caller leaves it open: 64 rows per wavefront (256-row tiles) at d = 128
     with fp16 inputs and |scale| <= 2/sqrt(d) (None: the usual 1/sqrt(d)) if every workgroup of a domain then
-    still gets two tiles of a head (four under the causal mask), and the caller did not ask for more
+    still gets a tile of a head (two under the causal mask), and the caller did not ask for more
     workgroups per domain than fit that way."""
     if d != 128 or dtype != "f16" or slots_per_domain > 32 or (scale is not None and scale * scale * d > 4.0):
         return 32
     parts = DOMAINS // gcd(heads, DOMAINS)
-    return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= (128 if causal else 64) else 32
+    return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= (64 if causal else 32) else 32
 
 
 def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",

@@ -43,8 +43,9 @@ SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b);
 
 // Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
 // workgroup tiles) for head dimension 128 and binary16 inputs once the steady state dominates, i.e.
-// every resident workgroup of a domain gets at least two full-length tiles of a head (four under the
-// causal mask, where a tile walks half the keys on average); 32 rows otherwise.  The wide variant
+// every resident workgroup of a domain gets at least one full-length tile of a head (two under the
+// causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured break-even:
+// +7 % and more from there on, a loss below.)  The wide variant
 // rounds scale*log2(e)*Q to binary16, which costs accuracy in proportion to the size of the scores;
 // it is therefore only chosen for |scale| <= 2/sqrt(d), twice the usual softmax scale.
 SAW_HD bool wide_scale_ok(float scale, int d) { return scale * scale * (float)d <= 4.0f; }
@@ -52,7 +53,7 @@ SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool
     if (d != 128 || bf16 || !wide_scale_ok(scale, d)) return 32;
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
-    return (wide_tiles + parts - 1) / parts >= (causal ? 128 : 64) ? 64 : 32;
+    return (wide_tiles + parts - 1) / parts >= (causal ? 64 : 32) ? 64 : 32;
 }
 
 // Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head

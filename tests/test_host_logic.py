@@ -168,15 +168,19 @@ def test_schedule_oracle_hand_example_wide_tiles():
     n_kv = 256 * 70 // 64
     assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 58, n_kv - 1, 0), (3, 69, 0, n_kv - 1)]
     assert s[7 * 8 + 3] == [(3, 7, 0, n_kv - 1), (3, 56, n_kv - 1, 0)]
-    # shorter sequences, head dimension 64, bfloat16 inputs, a causal mask on fewer than 128 tiles, or a request
-    # for more than 32 workgroups per domain keep 128-row tiles
-    assert so.launch_geometry(1, 8, 256 * 63)["tile_q"] == 128
+    # shorter sequences (fewer than 32 tiles per domain share of a head, 64 under the causal mask), head
+    # dimension 64, bfloat16 inputs, a scale beyond 2/sqrt(d), or a request for more than 32 workgroups per
+    # domain keep 128-row tiles
+    assert so.launch_geometry(1, 8, 256 * 31)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 32)["tile_q"] == 256
     assert so.launch_geometry(1, 8, 256 * 70, d=64)["tile_q"] == 128
     assert so.launch_geometry(1, 8, 256 * 70, dtype="bf16")["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 70, causal=True)["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 128, causal=True)["tile_q"] == 256
+    assert so.launch_geometry(1, 8, 256 * 70, scale=0.5)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 63, causal=True)["tile_q"] == 128
+    assert so.launch_geometry(1, 8, 256 * 64, causal=True)["tile_q"] == 256
     assert so.launch_geometry(1, 8, 256 * 70, slots_per_domain=64)["tile_q"] == 128
-    assert so.launch_geometry(1, 1, 256 * 8 * 64)["tile_q"] == 256      # one head over all 8 domains: 64 tiles each
+    assert so.launch_geometry(1, 1, 256 * 8 * 32)["tile_q"] == 256      # one head over all 8 domains: 32 tiles each
+    assert so.launch_geometry(1, 1, 256 * 8 * 31)["tile_q"] == 128
 
 
 # ------------------------------------------------------------------ host plan == oracle
@@ -260,7 +264,7 @@ def test_default_rows_per_wavefront_depends_on_dtype_length_and_scale(sa, causal
     """64 rows per wavefront is the default only where it is both faster and as accurate: d = 128, binary16
     inputs, long sequences, |scale| <= 2/sqrt(d) (it rounds scale*log2(e)*Q to binary16)."""
     H, d = 8, 128
-    N = 256 * (128 if causal else 64)
+    N = 256 * (64 if causal else 32)
     usual = 1.0 / math.sqrt(d)
     for dtype, n, scale, rows in (("f16", N, None, 64), ("f16", N, usual, 64), ("f16", N, -2.0 * usual, 64),
                                   ("f16", N, 2.01 * usual, 32), ("f16", N, 1.0, 32), ("bf16", N, None, 32),
