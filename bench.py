@@ -27,14 +27,14 @@ MFMA_PEAK_TFLOPS_16BIT = 2500.0   # MI355X dense fp16/bf16 matrix peak
 # script (summaries and commands under profiles/), scaled by the reading of the same counter for a
 # plain copy of known size.  Keyed by (workload, scan order); absent = not measured.
 MEASURED_TRAFFIC_BYTES: dict = {
-    (4, "sawtooth"): 8.2761e8, (4, "cyclic"): 8.4839e8,      # profiles/attn_fwd_cfg4_*.txt
+    (4, "sawtooth"): 8.0437e8, (4, "cyclic"): 8.0587e8,      # profiles/attn_fwd_cfg4_*.txt
     (5, "sawtooth"): 1.0930e10, (5, "cyclic"): 1.5124e10,    # profiles/attn_fwd_cfg5_*.txt
     (3, "sawtooth"): 1.7094e8, (3, "cyclic"): 1.7101e8,      # profiles/attn_fwd_cfg3_*.txt
     (2, "sawtooth"): 8.6362e6, (2, "cyclic"): 8.6362e6,      # profiles/attn_fwd_cfg2_*.txt
 }
 # TCC (L2) miss requests per launch from `rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum`.
 MEASURED_TCC_MISS: dict = {
-    (4, "sawtooth"): 6.465e6, (4, "cyclic"): 6.628e6,
+    (4, "sawtooth"): 6.282e6, (4, "cyclic"): 6.294e6,
     (5, "sawtooth"): 8.536e7, (5, "cyclic"): 1.1846e8,
     (3, "sawtooth"): 1.3344e6, (3, "cyclic"): 1.3344e6,
 }

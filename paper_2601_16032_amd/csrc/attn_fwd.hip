@@ -23,9 +23,10 @@
 // plus, at one end, a short run of masked tiles (general_range).  The workgroups of one XCD walk
 // the same head together and re-align between heads (domain_sync).
 //
-// For head dimension 128 there is a second tile shape (NH = 2 in the templates, pipelined_range_wide):
-// a wavefront owns two such 32-row halves, a workgroup 256 query rows, one workgroup per CU, and
-// every K / V^T fragment read from LDS feeds one MFMA per half.
+// For head dimension 128 and binary16 inputs there is a second tile shape (NH = 2 in the templates,
+// pipelined_range_wide): a wavefront owns two such 32-row halves, a workgroup 256 query rows, one
+// workgroup per CU, every K / V^T fragment read from LDS feeds one MFMA per half, and scale*log2(e) is
+// folded into Q so that the MFMAs deliver the exponent arguments directly.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -952,16 +953,6 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             u4 a[NA];   // indexed by n
             a[0] = ak[0];
             a[1] = ak[1];
-            auto constexpr_fetch = [&](int li) {
-                if (li == 0) load_to_lds_16B_at<0>(kbase, lm.fill_src[0], kdst_s);
-                if (li == 1) load_to_lds_16B_at<4096>(kbase, lm.fill_src[1], kdst_s);
-                if (li == 2) load_to_lds_16B_at<8192>(kbase, lm.fill_src[2], kdst_s);
-                if (li == 3) load_to_lds_16B_at<12288>(kbase, lm.fill_src[3], kdst_s);
-                if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
-                if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
-                if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
-                if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
-            };
             // Fragments are read from LDS two at a time, one pair ahead, and used in the order second, first:
             // the one wait for the later read covers both (half as many waits in the instruction stream).
 #pragma unroll
@@ -991,7 +982,6 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                         sum_pair(w0 & 1, w0 >> 1);
                         sum_pair((w0 + 1) & 1, (w0 + 1) >> 1);
                     }
-                    if (h == 0 && (q & 1) == 0) constexpr_fetch(q / 2);      // 8 loads over 16 fragments
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -1007,11 +997,21 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
         //      converts overwrite pf[.][0] (free after slot 7) and pf[.][1] (free after slot 15).
         float mx[2] = {0.f, 0.f};
         bool need = false;
+        auto constexpr_fetch = [&](int li) {
+            if (li == 0) load_to_lds_16B_at<0>(kbase, lm.fill_src[0], kdst_s);
+            if (li == 1) load_to_lds_16B_at<4096>(kbase, lm.fill_src[1], kdst_s);
+            if (li == 2) load_to_lds_16B_at<8192>(kbase, lm.fill_src[2], kdst_s);
+            if (li == 3) load_to_lds_16B_at<12288>(kbase, lm.fill_src[3], kdst_s);
+            if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
+            if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
+            if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
+            if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
+        };
 #pragma unroll
         for (int idx = 0; idx < NB; ++idx) {
             if (idx == NB / 2) {
-                // ---- everything fetched before this iteration has landed; publish it
-                asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+                // ---- everything fetched before this iteration has landed (all but its own first two loads); publish it
+                asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
                 __syncthreads();
             }
             if ((idx & 1) == 0) {
@@ -1023,6 +1023,9 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             for (int h = 0; h < 2; ++h) {
                 const int t = 2 * idx + h;
                 mfma_o(st[h].o[f % DB], av[f], pf[h][f / DB]);
+                // the fetches sit in the slots with no other work: two before the barrier, six at the end
+                if (t < 2) constexpr_fetch(t);
+                if (t >= 26) constexpr_fetch(t - 24);
                 if (t >= 2 && t < 10) {
                     // four maxima per slot, the two halves' chains alternating
 #pragma unroll
