@@ -55,17 +55,20 @@ def parse():
                     help="also run one plain 1 GiB device copy (reference reading for FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--ramp-ms", type=float, default=60.0,
                     help="untimed launches for this long before the warm-up steps, so that the clock has settled")
+    ap.add_argument("--workspace", action="store_true",
+                    help="bf16 workloads: call attn_fwd_workspace with a caller-allocated workspace (binary16 copies "
+                         "of K and V feed the 64-rows-per-wavefront kernel where it applies) instead of attn_fwd")
     ap.add_argument("--evict", action="store_true",
                     help="overwrite a 1 GiB scratch buffer before every step so each launch starts cache-cold")
     return ap.parse_args()
 
 
-def time_order(sa, torch, Q, K, V, O, w, order, steps, warmup, evict_buf=None):
+def time_order(launch, torch, order, steps, warmup, evict_buf=None):
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
         if evict_buf is not None:
             evict_buf.zero_()
-        sa.attn_fwd(Q, K, V, O, scale=w.scale, causal=w.causal, scan_order=order)
+        launch(order, stream)
     torch.cuda.synchronize()
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
     stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
@@ -74,7 +77,7 @@ def time_order(sa, torch, Q, K, V, O, w, order, steps, warmup, evict_buf=None):
         if evict_buf is not None:
             evict_buf.zero_()
         starts[i].record(stream)
-        sa.attn_fwd(Q, K, V, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream)
+        launch(order, stream)
         stops[i].record(stream)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
@@ -170,7 +173,19 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype)
+    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype, scale=w.scale)
+    ws, ws_bytes = None, 0
+    if args.workspace:
+        ws_bytes, info = sa.attn_fwd_workspace_bytes(w.B, w.H, w.N, w.d, w.causal, None, w.dtype, w.scale)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+
+    def launch(order, stream):
+        if ws is not None:
+            sa.attn_fwd_workspace(Qd, Kd, Vd, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream,
+                                  workspace=ws)
+        else:
+            sa.attn_fwd(Qd, Kd, Vd, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream)
+
     orders = ["sawtooth", "cyclic"] if args.scan_order == "both" else [args.scan_order]
     # Bring the chip to the clock it sustains under this kernel before anything is timed: it leaves idle at a low
     # clock and settles, under matrix load, well below its peak clock within some tens of milliseconds.  Without
@@ -178,11 +193,11 @@ def main():
     t_ramp = time.perf_counter()
     while time.perf_counter() - t_ramp < args.ramp_ms * 1e-3:
         for _ in range(4):
-            sa.attn_fwd(Qd, Kd, Vd, O, scale=w.scale, causal=w.causal, scan_order=orders[0])
+            launch(orders[0], torch.cuda.current_stream())
         torch.cuda.synchronize()
     res = {}
     for order in orders:
-        wall_ms, kernel_ms = time_order(sa, torch, Qd, Kd, Vd, O, w, order, args.steps, args.warmup, evict_buf)
+        wall_ms, kernel_ms = time_order(launch, torch, order, args.steps, args.warmup, evict_buf)
         res[order] = {"ms_per_step": wall_ms, "kernel_ms": kernel_ms,
                       "tflops": w.flops / (kernel_ms * 1e-3) / 1e12,
                       "tflops_wall": w.flops / (wall_ms * 1e-3) / 1e12}
@@ -203,13 +218,16 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": w.causal,
                    "scan_order": head, "out_dtype": str(o_dtype).replace("torch.", ""), "flops_per_step": w.flops,
-                   "launch": info, "cache_cold_steps": bool(args.evict)},
+                   "launch": info, "cache_cold_steps": bool(args.evict),
+                   "entry_point": "attn_fwd_workspace" if ws is not None else "attn_fwd", "workspace_bytes": ws_bytes},
         "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_PEAK_TFLOPS_16BIT,
                      "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_PEAK_TFLOPS_16BIT,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, head)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, head, "workspace") if ws_bytes
+                                                           else (args.workload, head)),
                      "kernel_ms": r["kernel_ms"]},
         "scan_orders": {o: {"tflops": res[o]["tflops"], "kernel_ms": res[o]["kernel_ms"],
-                            "tcc_miss": MEASURED_TCC_MISS.get((args.workload, o))} for o in orders},
+                            "tcc_miss": MEASURED_TCC_MISS.get((args.workload, o, "workspace") if ws_bytes
+                                                              else (args.workload, o))} for o in orders},
     }
     if not args.no_mfma_probe:
         out["mfma_probe"] = mfma_probe(sa, torch)

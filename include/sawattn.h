@@ -10,6 +10,7 @@
 #ifndef SAWATTN_H
 #define SAWATTN_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -145,6 +146,39 @@ typedef struct sawattn_launch_info {
     int q_tiles_per_head;  /* ceil(N / tile_q) */
     int max_local_tiles;   /* most query tiles any one workgroup processes */
 } sawattn_launch_info;
+
+/*
+ * attn_fwd_workspace -- attn_fwd_variant with scratch memory from the caller (paper Sec. 2.2, Alg. 1: the same
+ * kernel; the scratch only changes the element type K and V are streamed in).  bfloat16 inputs normally run the
+ * 32-rows-per-wavefront kernel, because the faster 64-row kernel needs binary16 operands.  Given a workspace, and
+ * where that kernel would be chosen for the same problem in binary16 (d = 128, |scale| <= 2/sqrt(d), sequence long
+ * enough; or variant.rows_per_wavefront = 64), the call first writes binary16 copies of K and V into the
+ * workspace with one extra kernel on the same stream and then runs the 64-row kernel on them, converting Q as it
+ * is loaded.  The copies are exact for bfloat16 magnitudes in [2^-14, 65504] and rounded to binary16 subnormals
+ * below (absolute error under 2^-25); larger K or V values are not supported on this path (V has that limit in
+ * attn_fwd as well).  In every other case the call is attn_fwd_variant
+ * and the workspace is not touched.
+ *
+ *   workspace        device, written, 16-byte aligned, must not overlap Q, K, V or O; may be NULL (then this is
+ *                    attn_fwd_variant).  Only used during the kernels this call enqueues.
+ *   workspace_bytes  its size; at least what attn_fwd_workspace_bytes reports, else INVALID_ARG.
+ * Nothing is allocated by the library.  All other arguments, errors and stream behaviour as attn_fwd_variant;
+ * the launch geometry (for trace) is what attn_fwd_workspace_bytes reports in `info`.
+ */
+int attn_fwd_workspace(const void* Q, const void* K, const void* V, void* O,
+                       int B, int H, int N, int d, float scale, int causal, int scan_order,
+                       int in_dtype, int o_dtype, void* hip_stream,
+                       const sawattn_variant* variant, int32_t* trace, int32_t* trace_count,
+                       void* workspace, size_t workspace_bytes);
+
+/*
+ * attn_fwd_workspace_bytes -- how much workspace attn_fwd_workspace would use for a problem: 4*B*H*N*d bytes
+ * (binary16 copies of K and V) where the conversion path applies, 0 where it does not (then a workspace changes
+ * nothing).  `bytes` and `info` are host memory; `info` may be NULL, else it receives the launch geometry of the
+ * kernel attn_fwd_workspace would run.  Validation as attn_fwd_launch_info.  Launches nothing.
+ */
+int attn_fwd_workspace_bytes(int B, int H, int N, int d, float scale, int causal, int in_dtype,
+                             const sawattn_variant* variant, size_t* bytes, sawattn_launch_info* info);
 
 /*
  * attn_fwd_launch_info -- report the geometry attn_fwd (variant NULL) or attn_fwd_variant would use

@@ -78,6 +78,11 @@ def lib() -> ctypes.CDLL:
         pv = ctypes.POINTER(Variant)
         L.attn_fwd_variant.restype = ci
         L.attn_fwd_variant.argtypes = L.attn_fwd.argtypes + [pv, vp, vp]
+        L.attn_fwd_workspace.restype = ci
+        L.attn_fwd_workspace.argtypes = L.attn_fwd_variant.argtypes + [vp, ctypes.c_size_t]
+        L.attn_fwd_workspace_bytes.restype = ci
+        L.attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, pv, ctypes.POINTER(ctypes.c_size_t),
+                                               ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_launch_info.restype = ci
         L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, pv, ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_plan.restype = ci
@@ -131,6 +136,16 @@ def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_ord
     _check(lib().attn_fwd_plan(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _SCAN_CODE[scan_order],
                                _in_dtype_code(dtype), _vptr(variant), trace.data_ptr(), count.data_ptr()))
     return trace, count
+
+
+def attn_fwd_workspace_bytes(B: int, H: int, N: int, d: int, causal: bool = False, variant: Variant = None,
+                             dtype="bf16", scale: float = None):
+    """(bytes of workspace attn_fwd_workspace would use -- 0 where it changes nothing --, launch geometry)."""
+    n = ctypes.c_size_t(0)
+    info = LaunchInfo()
+    _check(lib().attn_fwd_workspace_bytes(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _in_dtype_code(dtype),
+                                          _vptr(variant), ctypes.byref(n), ctypes.byref(info)))
+    return int(n.value), info.as_dict()
 
 
 def sawattn_mfma_probe(iters: int, mode: int, stream=None) -> float:
@@ -187,3 +202,28 @@ def attn_fwd_variant(Q, K, V, O=None, *, scale: float, causal: bool = False, sca
                                   _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream, _vptr(variant),
                                   tr.data_ptr() if trace else None, cnt.data_ptr() if trace else None))
     return (O, tr, cnt) if trace else O
+
+
+def attn_fwd_workspace(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order="sawtooth",
+                       o_dtype=None, stream=None, variant: Variant = None, trace: bool = False, workspace=None):
+    """attn_fwd_variant with a workspace (a uint8 CUDA tensor of at least attn_fwd_workspace_bytes bytes; allocated
+    here when None and needed).  Returns like attn_fwd_variant."""
+    O = _marshal(Q, K, V, O, o_dtype)
+    B, H, N, d = Q.shape
+    need, info = attn_fwd_workspace_bytes(B, H, N, d, causal, variant, Q.dtype, scale)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    tr = cnt = None
+    if trace:
+        tr = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32,
+                        device=Q.device)
+        cnt = torch.zeros((info["grid"],), dtype=torch.int32, device=Q.device)
+    st = stream if stream is not None else torch.cuda.current_stream(Q.device)
+    _check(lib().attn_fwd_workspace(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                    float(scale), int(bool(causal)), _SCAN_CODE[scan_order],
+                                    _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream, _vptr(variant),
+                                    tr.data_ptr() if trace else None, cnt.data_ptr() if trace else None,
+                                    workspace.data_ptr() if workspace is not None else None,
+                                    workspace.numel() if workspace is not None else 0))
+    return (O, tr, cnt) if trace else O
+

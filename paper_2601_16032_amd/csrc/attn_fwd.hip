@@ -29,6 +29,7 @@
 // folded into Q so that the MFMAs deliver the exponent arguments directly.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
@@ -69,6 +70,7 @@ struct Params {
     int o_dtype;
     int sawtooth;
     int negate_q;          // scale < 0: use -Q and |scale|
+    int q_bf16;            // wide variant on converted inputs: Q is still bfloat16 (K and V are binary16 copies)
     int max_local;
     float c;               // |scale| * log2(e): scores are handled in the log2 domain
     Schedule sched;
@@ -1174,8 +1176,14 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     const unsigned word = v[w];   // (a copy: bit casts of a vector element do not read that element)
-                    const f2 x = __builtin_convertvector(__builtin_bit_cast(h2, word), f2) * p.c;
-                    v[w] = __builtin_bit_cast(unsigned, __builtin_convertvector(x, h2));
+                    f2 x;
+                    if (p.q_bf16) {
+                        x[0] = __builtin_bit_cast(float, word << 16);
+                        x[1] = __builtin_bit_cast(float, word & 0xffff0000u);
+                    } else {
+                        x = __builtin_convertvector(__builtin_bit_cast(h2, word), f2);
+                    }
+                    v[w] = __builtin_bit_cast(unsigned, __builtin_convertvector(x * p.c, h2));
                 }
                 asm volatile("" : "=a"(st[h].qf[ks]) : "0"(v));   // accumulation registers from here on
             } else {
@@ -1250,6 +1258,16 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
                     }
                 }
         }
+    }
+}
+
+// bfloat16 -> binary16 copies of K and V for the workspace path (16 bytes per lane and step).
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const u4* __restrict__ K, const u4* __restrict__ V,
+                                                          u4* __restrict__ K16, u4* __restrict__ V16, size_t chunks) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < chunks; i += stride) {
+        K16[i] = bf16x8_to_f16x8(K[i]);
+        V16[i] = bf16x8_to_f16x8(V[i]);
     }
 }
 
@@ -1478,9 +1496,21 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, float scale
     return SAWATTN_OK;
 }
 
+// Whether bfloat16 inputs, converted to binary16, would run the wide variant: then a workspace pays.
+int workspace_schedule(int B, int H, int N, int d, bool causal, bool bf16, float scale, const sawattn_variant* v,
+                       Schedule* out, bool* use) {
+    *use = false;
+    if (!bf16 || d != 128) return SAWATTN_OK;
+    Schedule s;
+    const int rc = schedule_for(B, H, N, d, causal, false, scale, v, &s);
+    if (rc != SAWATTN_OK) return rc;
+    if (s.tile_q > kTileQ) { *use = true; *out = s; }
+    return SAWATTN_OK;
+}
+
 int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale, int causal,
         int scan_order, int in_dtype, int o_dtype, void* hip_stream, const sawattn_variant* variant, int32_t* trace,
-        int32_t* trace_count) {
+        int32_t* trace_count, void* workspace = nullptr, size_t workspace_bytes = 0) {
     int rc = check_shape(B, H, N, d);
     if (rc != SAWATTN_OK) return rc;
     if (!Q || !K || !V || !O) return fail(SAWATTN_ERR_INVALID_ARG, "Q, K, V and O must be non-null");
@@ -1496,8 +1526,15 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     if ((trace == nullptr) != (trace_count == nullptr))
         return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be given together");
     Schedule sched;
-    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &sched);
-    if (rc != SAWATTN_OK) return rc;
+    bool converted = false;   // bfloat16 inputs through binary16 copies of K and V in the caller's workspace
+    if (workspace) {
+        rc = workspace_schedule(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &sched, &converted);
+        if (rc != SAWATTN_OK) return rc;
+    }
+    if (!converted) {
+        rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &sched);
+        if (rc != SAWATTN_OK) return rc;
+    }
     {   // A workgroup writes its O rows while others still read Q, K, V: O may not share memory with them.
         const unsigned long long elems = (unsigned long long)B * H * N * d;
         const unsigned long long in_bytes = elems * 2u, out_bytes = elems * (o_dtype == SAWATTN_F32 ? 4u : 2u);
@@ -1505,6 +1542,17 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         for (const void* in : {Q, K, V}) {
             const uintptr_t i0 = (uintptr_t)in, i1 = i0 + in_bytes;
             if (o0 < i1 && i0 < o1) return fail(SAWATTN_ERR_INVALID_ARG, "O must not overlap Q, K or V");
+        }
+        if (converted) {
+            if ((uintptr_t)workspace & 15u) return fail(SAWATTN_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+            if (workspace_bytes < 2 * in_bytes)
+                return fail(SAWATTN_ERR_INVALID_ARG, "workspace is smaller than attn_fwd_workspace_bytes reports");
+            const uintptr_t w0 = (uintptr_t)workspace, w1 = w0 + 2 * in_bytes;
+            for (const void* in : {Q, K, V}) {
+                const uintptr_t i0 = (uintptr_t)in, i1 = i0 + in_bytes;
+                if (w0 < i1 && i0 < w1) return fail(SAWATTN_ERR_INVALID_ARG, "workspace must not overlap Q, K, V or O");
+            }
+            if (w0 < o1 && o0 < w1) return fail(SAWATTN_ERR_INVALID_ARG, "workspace must not overlap Q, K, V or O");
         }
     }
 
@@ -1515,12 +1563,25 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.o_dtype = o_dtype;
     p.sawtooth = scan_order == SAWATTN_SCAN_SAWTOOTH;
     p.negate_q = scale < 0.f;
+    p.q_bf16 = converted;
     p.c = (float)(std::fabs((double)scale) * 1.4426950408889634074);
     p.sched = sched;
     p.max_local = sched.local_iters;
     const int grid = sched.grid;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool bf = in_dtype == SAWATTN_BF16, ca = causal != 0;
+    if (converted) {
+        const size_t chunks = (size_t)B * H * N * d / 8;
+        u4* K16 = static_cast<u4*>(workspace);
+        u4* V16 = K16 + chunks;
+        const unsigned blocks = (unsigned)std::min<size_t>((chunks + 255) / 256, 256 * 16);
+        hipLaunchKernelGGL(bf16_to_f16_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const u4*>(K),
+                           static_cast<const u4*>(V), K16, V16, chunks);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(SAWATTN_ERR_RUNTIME, "conversion kernel launch failed");
+        p.K = K16;
+        p.V = V16;
+    }
     if (sched.tile_q > kTileQ) {
         return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
@@ -1547,6 +1608,36 @@ int attn_fwd_variant(const void* Q, const void* K, const void* V, void* O, int B
                      const sawattn_variant* variant, int32_t* trace, int32_t* trace_count) {
     return sawattn::run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, variant, trace,
                         trace_count);
+}
+
+int attn_fwd_workspace(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                       int causal, int scan_order, int in_dtype, int o_dtype, void* hip_stream,
+                       const sawattn_variant* variant, int32_t* trace, int32_t* trace_count, void* workspace,
+                       size_t workspace_bytes) {
+    return sawattn::run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, variant, trace,
+                        trace_count, workspace, workspace_bytes);
+}
+
+int attn_fwd_workspace_bytes(int B, int H, int N, int d, float scale, int causal, int in_dtype,
+                             const sawattn_variant* variant, size_t* bytes, sawattn_launch_info* info) {
+    using namespace sawattn;
+    if (!bytes) return fail(SAWATTN_ERR_INVALID_ARG, "bytes must be non-null");
+    if (!std::isfinite(scale)) return fail(SAWATTN_ERR_INVALID_ARG, "scale must be finite");
+    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
+        return fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
+    int rc = check_shape(B, H, N, d);
+    if (rc != SAWATTN_OK) return rc;
+    Schedule s;
+    bool use = false;
+    rc = workspace_schedule(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s, &use);
+    if (rc != SAWATTN_OK) return rc;
+    if (!use) {
+        rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s);
+        if (rc != SAWATTN_OK) return rc;
+    }
+    *bytes = use ? (size_t)B * H * N * d * 4 : 0;
+    if (info) fill_info(s, d, info);
+    return SAWATTN_OK;
 }
 
 int attn_fwd_launch_info(int B, int H, int N, int d, float scale, int causal, int in_dtype,

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2601_16032_amd import workloads
+from paper_2601_16032_amd import binding, workloads
 from tests.util import REL_L2_TOL, assert_close, errors
 
 pytestmark = pytest.mark.gpu
@@ -367,3 +367,88 @@ def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal):
     torch.cuda.synchronize()
     want = oracle.attention(Q, K, V, 1.0, causal=causal, rows=rows)
     assert_close(got.double().cpu().numpy()[:, :, rows], want, f"scale 1 causal={causal}")
+
+
+# ------------------------------------------------------------------ bfloat16 through binary16 copies in a workspace
+@pytest.mark.parametrize("causal", [False, True])
+def test_workspace_path_small_shapes(sa, oracle, causal):
+    """bfloat16 inputs with a workspace and 64 rows per wavefront: K and V go through binary16 copies, Q is
+    converted as it is loaded.  Every length class, both scan orders, schedule as for binary16 inputs; the caller's
+    tensors stay untouched; without a workspace the same request is refused."""
+    from oracle import schedule_oracle as so
+    var = sa.variant(rows_per_wavefront=64)
+    for k, N in enumerate([1, 63, 64, 65, 200, 256, 257, 511, 777, 2048 + 33]):
+        B, H = (1, 2) if k % 2 == 0 else (2, 3)
+        Q, K, V = workloads.make_random(B, H, N, 128, "bf16", seed=3000 + N)
+        scale = 1.0 / math.sqrt(128)
+        want = oracle.attention(Q, K, V, scale, causal=causal)
+        Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+        need, info = sa.attn_fwd_workspace_bytes(B, H, N, 128, causal, var, "bf16")
+        assert need == 4 * B * H * N * 128 and info["tile_q"] == 256
+        ws = torch.full((need + 64,), 0x5A, dtype=torch.uint8, device="cuda")
+        for order in ORDERS:
+            O, trace, count = sa.attn_fwd_workspace(Qd, Kd, Vd, scale=scale, causal=causal, scan_order=order,
+                                                    o_dtype=torch.float32, variant=var, trace=True, workspace=ws[:need])
+            torch.cuda.synchronize()
+            assert_close(O.double().cpu().numpy(), want, f"workspace N={N} causal={causal} {order}")
+            sched = so.schedule(B, H, N, causal, order, d=128, rows_per_wavefront=64)
+            trace, count = trace.cpu(), count.cpu()
+            for wg, recs in sched.items():
+                assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == recs, f"workgroup {wg}"
+        assert torch.equal(Qd.cpu(), Q) and torch.equal(Kd.cpu(), K) and torch.equal(Vd.cpu(), V)
+        assert bool((ws[need:] == 0x5A).all()), "wrote past the reported size"
+        # the copies are the inputs rounded to binary16 (exact from 2^-14 up)
+        half = ws[:need].view(torch.float16)
+        assert torch.equal(half[: half.numel() // 2].view(B, H, N, 128).cpu(), K.float().half())
+        assert torch.equal(half[half.numel() // 2:].view(B, H, N, 128).cpu(), V.float().half())
+        big = K.float().abs() >= 2.0 ** -14
+        assert torch.equal(K.float().half().float()[big], K.float()[big])
+    with pytest.raises(binding.SawattnError) as e:
+        sa.attn_fwd_variant(Qd, Kd, Vd, scale=scale, causal=causal, variant=var)
+    assert e.value.code == binding.ERR_UNSUPPORTED
+    with pytest.raises(binding.SawattnError) as e:     # too small a workspace
+        sa.attn_fwd_workspace(Qd, Kd, Vd, scale=scale, causal=causal, variant=var, workspace=ws[: need - 16])
+    assert e.value.code == binding.ERR_INVALID_ARG
+    with pytest.raises(binding.SawattnError) as e:     # a workspace inside an input
+        sa.attn_fwd_workspace(Qd, Kd, Vd, scale=scale, causal=causal, variant=var,
+                              workspace=Kd.view(torch.uint8).flatten())
+    assert e.value.code == binding.ERR_INVALID_ARG
+
+
+def test_workspace_path_is_the_plain_path_where_it_does_not_apply(sa):
+    """Short bfloat16 sequences, binary16 inputs, d = 64: the result is attn_fwd's bit for bit and the workspace is
+    left alone."""
+    for (B, H, N, d, dtype, causal) in ((1, 4, 1000, 128, "bf16", True), (1, 8, 256 * 40, 128, "f16", False),
+                                        (2, 2, 700, 64, "bf16", False)):
+        Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=77, device="cuda")
+        scale = 1.0 / math.sqrt(d)
+        ws = torch.full((1 << 20,), 0x33, dtype=torch.uint8, device="cuda")
+        a = sa.attn_fwd(Q, K, V, scale=scale, causal=causal, scan_order="sawtooth", o_dtype=torch.float32)
+        b = sa.attn_fwd_workspace(Q, K, V, scale=scale, causal=causal, scan_order="sawtooth", o_dtype=torch.float32,
+                                  workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b) and bool((ws == 0x33).all())
+
+
+def test_workspace_path_at_full_size(sa, oracle):
+    """Workload 5 (bfloat16, causal, N = 32K) through the workspace, as bench.py times it: sampled rows against
+    the oracle, both scan orders, and against the plain 32-row path."""
+    w = workloads.WORKLOADS[5]
+    Q, K, V = workloads.make_qkv(w)
+    picks = [(0, 0), (w.B - 1, w.H - 1), (1, 7)]
+    rows = sample_rows(w.N, 555)
+    Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+    need, info = sa.attn_fwd_workspace_bytes(w.B, w.H, w.N, w.d, w.causal, None, "bf16", w.scale)
+    assert need == 4 * Q.numel() and info["tile_q"] == 256
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    plain = sa.attn_fwd(Qd, Kd, Vd, scale=w.scale, causal=True, scan_order="sawtooth", o_dtype=torch.float32)
+    wants = {(b, h): oracle.attention(Q[b:b + 1, h:h + 1], K[b:b + 1, h:h + 1], V[b:b + 1, h:h + 1], w.scale,
+                                      causal=True, rows=rows)[0, 0] for (b, h) in picks}
+    for order in ORDERS:
+        O = sa.attn_fwd_workspace(Qd, Kd, Vd, scale=w.scale, causal=True, scan_order=order, o_dtype=torch.float32,
+                                  workspace=ws)
+        torch.cuda.synchronize()
+        for (b, h) in picks:
+            e = assert_close(O[b, h][rows].double().cpu().numpy(), wants[(b, h)], f"workload 5 workspace {order} ({b},{h})")
+            print("workspace", (b, h), order, "max-abs %.2e rel-L2 %.2e" % e, flush=True)
+        assert_close(O[0, :4].double().cpu().numpy(), plain[0, :4].double().cpu().numpy(), f"workspace vs plain {order}")

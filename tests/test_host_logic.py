@@ -27,6 +27,7 @@ def test_library_exports_every_declared_symbol(sa):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", header)
     assert set(names) >= {"attn_fwd", "attn_fwd_variant", "attn_fwd_launch_info", "attn_fwd_plan",
+                          "attn_fwd_workspace", "attn_fwd_workspace_bytes",
                           "sawattn_mfma_probe", "sawattn_last_error", "sawattn_version"}
     L = sa.lib()
     for n in names:
@@ -277,6 +278,29 @@ def test_default_rows_per_wavefront_depends_on_dtype_length_and_scale(sa, causal
     with pytest.raises(binding.SawattnError) as e:
         sa.attn_fwd_launch_info(1, H, N, d, causal, scale=float("inf"))
     assert e.value.code == binding.ERR_INVALID_ARG
+
+
+def test_workspace_bytes_follow_the_choice_of_kernel(sa):
+    """A workspace is asked for exactly where bfloat16 inputs, once converted, would run the 64-row kernel."""
+    usual = None
+    for (B, H, N, d, causal, dtype, kw, scale, want_rows) in (
+            (4, 32, 32768, 128, True, "bf16", {}, usual, 64),            # workload 5
+            (1, 16, 8192, 128, True, "bf16", {}, usual, 32),             # workload 3: too short under the mask
+            (1, 16, 8192, 128, False, "bf16", {}, usual, 64),
+            (1, 16, 8192, 128, True, "bf16", dict(rows_per_wavefront=64), usual, 64),
+            (1, 16, 32768, 128, False, "bf16", dict(rows_per_wavefront=32), usual, 32),
+            (1, 16, 32768, 128, False, "bf16", {}, 1.0, 32),              # scale beyond 2/sqrt(d)
+            (1, 8, 32768, 64, False, "bf16", {}, usual, 32),
+            (1, 32, 16384, 128, False, "f16", {}, usual, 64)):            # binary16 needs no copies
+        var = sa.variant(**kw) if kw else None
+        need, info = sa.attn_fwd_workspace_bytes(B, H, N, d, causal, var, dtype, scale)
+        assert info["tile_q"] == 4 * want_rows, (B, H, N, d, causal, dtype, kw, scale)
+        assert need == (4 * B * H * N * d if dtype == "bf16" and want_rows == 64 else 0)
+        # the geometry is the binary16 one where copies are made, the plain one elsewhere
+        as_if = "f16" if need else dtype
+        assert info == sa.attn_fwd_launch_info(B, H, N, d, causal, var, as_if, scale)
+    with pytest.raises(binding.SawattnError):
+        sa.attn_fwd_workspace_bytes(1, 8, 2048, 80, False)
 
 
 # ------------------------------------------------------------------ traffic model vs the paper's counters
