@@ -808,7 +808,7 @@ constexpr int kWideBuffers = 4;
 constexpr int kWideLdsBytes = 2 * kWideBuffers * Geo<128>::kTile;
 
 __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], const LaneMap<128>& lm, const char* Kh,
-                                                     const char* Vh, int j_first, int step, int count, int lane,
+                                                     const char* Vh, int j_first, int step, int count,
                                                      LDS_PTR(char) lds) {
     constexpr int D = 128;
     using G = Geo<D>;
@@ -1215,7 +1215,7 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             int l2 = lane;
             asm volatile("" : "+v"(l2));
             const LaneMap<D> lm2(wave, l2);
-            pipelined_range_wide(st, lm2, Kh, Vh, j_first, step, n_plain, l2, lds);
+            pipelined_range_wide(st, lm2, Kh, Vh, j_first, step, n_plain, lds);
         }
     };
     auto masked = [&](int j_first) {
