@@ -369,6 +369,47 @@ def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal):
     assert_close(got.double().cpu().numpy()[:, :, rows], want, f"scale 1 causal={causal}")
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_wide_kernel_random_shapes_and_score_patterns(sa, oracle, seed):
+    """Seeded random cases for the 64-rows-per-wavefront kernel (bf16 ones through the workspace): lengths around
+    the tile boundaries, few slots (many rounds), both launches and orders, and three score patterns -- plain
+    N(0,1), levels that jump between 64-key tiles by up to 40 score units, and a ramp that raises the maximum on
+    every tile in one scan direction and never in the other.  The patterned cases reach scores of 30 binades and
+    more, where the rounding of scale*log2(e)*Q (2^-11 relative) shows: they get 3e-3 (seen: up to 1.3e-3)."""
+    rng = np.random.default_rng(seed)
+    d, scale = 128, 1.0 / math.sqrt(128)
+    for case in range(30):
+        dtype = str(rng.choice(["f16", "bf16"]))
+        causal = bool(rng.integers(0, 2))
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        N = int(rng.choice([rng.integers(1, 70), rng.integers(60, 400), rng.integers(250, 1400), rng.integers(1000, 3000)]))
+        order = str(rng.choice(ORDERS))
+        g = torch.Generator("cpu").manual_seed(int(rng.integers(0, 1 << 30)))
+        Q, K, V = (torch.randn(B, H, N, d, generator=g) for _ in range(3))
+        mode = int(rng.integers(0, 3))
+        if mode == 1:
+            level = 40.0 * torch.rand(B, H, (N + 63) // 64, generator=g)
+            K[:, :, :, 0] = level.repeat_interleave(64, dim=2)[:, :, :N]
+            Q[:, :, :, 0] = 6.0
+        elif mode == 2:
+            K[:, :, :, 1] = torch.linspace(0, 60, N)
+            Q[:, :, :, 1] = 5.0 * (1 if rng.integers(0, 2) else -1)
+        dt = torch.float16 if dtype == "f16" else torch.bfloat16
+        Q, K, V = Q.to(dt), K.to(dt), V.to(dt)
+        want = oracle.attention(Q, K, V, scale, causal=causal)
+        var = sa.variant(rows_per_wavefront=64, slots_per_domain=int(rng.choice([0, 1, 2])),
+                         launch=str(rng.choice(["persistent", "grid"])))
+        call = sa.attn_fwd_workspace if dtype == "bf16" else sa.attn_fwd_variant
+        O = call(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order, o_dtype=torch.float32,
+                 variant=var)
+        torch.cuda.synchronize()
+        got = O.double().cpu().numpy()
+        max_abs, rel_l2 = errors(got, want)
+        what = f"case {case}: {dtype} B{B} H{H} N{N} causal={causal} {order} pattern {mode}"
+        assert np.isfinite(got).all(), what
+        assert max_abs <= (2e-3 if mode == 0 else 3e-3) and rel_l2 <= REL_L2_TOL, f"{what}: {max_abs:.3e} {rel_l2:.3e}"
+
+
 # ------------------------------------------------------------------ bfloat16 through binary16 copies in a workspace
 @pytest.mark.parametrize("causal", [False, True])
 def test_workspace_path_small_shapes(sa, oracle, causal):
