@@ -28,17 +28,17 @@ MFMA_PEAK_TFLOPS_16BIT = 2500.0   # MI355X dense fp16/bf16 matrix peak
 # plain copy of known size.  Keyed by (workload, scan order); absent = not measured.
 MEASURED_TRAFFIC_BYTES: dict = {
     (4, "sawtooth"): 8.0437e8, (4, "cyclic"): 8.0587e8,      # profiles/attn_fwd_cfg4_*.txt
-    (5, "sawtooth"): 1.0930e10, (5, "cyclic"): 1.5124e10,    # profiles/attn_fwd_cfg5_*.txt
-    (3, "sawtooth"): 1.7094e8, (3, "cyclic"): 1.7101e8,      # profiles/attn_fwd_cfg3_*.txt
-    (2, "sawtooth"): 8.6362e6, (2, "cyclic"): 8.6362e6,      # profiles/attn_fwd_cfg2_*.txt
+    (5, "sawtooth"): 1.1779e10, (5, "cyclic"): 1.2341e10,    # profiles/attn_fwd_cfg5_*.txt
+    (3, "sawtooth"): 1.7393e8, (3, "cyclic"): 1.7390e8,      # profiles/attn_fwd_cfg3_*.txt
+    (2, "sawtooth"): 8.6454e6, (2, "cyclic"): 8.6454e6,      # profiles/attn_fwd_cfg2_*.txt
     # --workspace: the conversion kernel (reads and writes 2 GiB) and the attention kernel of a launch together
     (5, "sawtooth", "workspace"): 1.2673e10, (5, "cyclic", "workspace"): 1.6393e10,   # profiles/attn_fwd_cfg5_*_workspace.txt
 }
 # TCC (L2) miss requests per launch from `rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum`.
 MEASURED_TCC_MISS: dict = {
     (4, "sawtooth"): 6.282e6, (4, "cyclic"): 6.294e6,
-    (5, "sawtooth"): 8.536e7, (5, "cyclic"): 1.1846e8,
-    (3, "sawtooth"): 1.3344e6, (3, "cyclic"): 1.3344e6,
+    (5, "sawtooth"): 9.201e7, (5, "cyclic"): 9.641e7,
+    (3, "sawtooth"): 1.3570e6, (3, "cyclic"): 1.3573e6,
     (5, "sawtooth", "workspace"): 9.899e7, (5, "cyclic", "workspace"): 1.2674e8,
 }
 
