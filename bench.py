@@ -23,24 +23,26 @@ sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS_16BIT = 2500.0   # MI355X dense fp16/bf16 matrix peak
 
-# HBM-side bytes per launch, from `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` runs of this
-# script (summaries and commands under profiles/), scaled by the reading of the same counter for a
-# plain copy of known size.  Keyed by (workload, scan order); absent = not measured.
-MEASURED_TRAFFIC_BYTES: dict = {
-    (4, "sawtooth"): 8.0437e8, (4, "cyclic"): 8.0587e8,      # profiles/attn_fwd_cfg4_*.txt
-    (5, "sawtooth"): 1.1779e10, (5, "cyclic"): 1.2341e10,    # profiles/attn_fwd_cfg5_*.txt
-    (3, "sawtooth"): 1.7393e8, (3, "cyclic"): 1.7390e8,      # profiles/attn_fwd_cfg3_*.txt
-    (2, "sawtooth"): 8.6454e6, (2, "cyclic"): 8.6454e6,      # profiles/attn_fwd_cfg2_*.txt
-    # --workspace: the conversion kernel (reads and writes 2 GiB) and the attention kernel of a launch together
-    (5, "sawtooth", "workspace"): 1.2673e10, (5, "cyclic", "workspace"): 1.6393e10,   # profiles/attn_fwd_cfg5_*_workspace.txt
-}
-# TCC (L2) miss requests per launch from `rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCC_REQ_sum`.
-MEASURED_TCC_MISS: dict = {
-    (4, "sawtooth"): 6.282e6, (4, "cyclic"): 6.294e6,
-    (5, "sawtooth"): 9.201e7, (5, "cyclic"): 9.641e7,
-    (3, "sawtooth"): 1.3570e6, (3, "cyclic"): 1.3573e6,
-    (5, "sawtooth", "workspace"): 9.899e7, (5, "cyclic", "workspace"): 1.2674e8,
-}
+
+
+def profiled_counters(workload_name: str, workspace: bool):
+    """HBM-side bytes and TCC (L2) misses per launch and scan order, read from the committed rocprofv3 summary of
+    this workload (profiles/attn_fwd_<workload>[_workspace].txt: `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` /
+    `TCC_MISS_sum` runs of this script, the byte counters scaled by their reading for a plain 1 GiB copy in the same
+    run).  They are profile figures, not measured in this run: the line names the file they come from.  Returns
+    (traffic bytes by order, misses by order, path relative to the repository) or ({}, {}, None) without a summary."""
+    rel = os.path.join("profiles", f"attn_fwd_{workload_name}" + ("_workspace" if workspace else "") + ".txt")
+    path = os.path.join(ROOT, rel)
+    traffic, misses = {}, {}
+    if not os.path.exists(path):
+        return traffic, misses, None
+    for line in open(path):
+        t = line.split()
+        if len(t) >= 3 and t[0] == "TCC_MISS_sum" and t[1] in ("sawtooth", "cyclic"):
+            misses[t[1]] = float(t[2])
+        if len(t) >= 4 and t[0] in ("sawtooth", "cyclic") and "bytes per launch" in line and "total" in t:
+            traffic[t[0]] = float(t[t.index("total") + 1])
+    return traffic, misses, rel
 
 
 def parse():
@@ -61,6 +63,8 @@ def parse():
     ap.add_argument("--workspace", action="store_true",
                     help="bf16 workloads: call attn_fwd_workspace with a caller-allocated workspace (binary16 copies "
                          "of K and V feed the 64-rows-per-wavefront kernel where it applies) instead of attn_fwd")
+    ap.add_argument("--rows-per-wavefront", type=int, default=0, choices=[0, 32, 64],
+                    help="0: what attn_fwd picks by itself; 32 or 64: that kernel shape through attn_fwd_variant")
     ap.add_argument("--evict", action="store_true",
                     help="overwrite a 1 GiB scratch buffer before every step so each launch starts cache-cold")
     return ap.parse_args()
@@ -176,16 +180,22 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype, scale=w.scale)
+    info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype)
+    var = sa.variant(rows_per_wavefront=args.rows_per_wavefront) if args.rows_per_wavefront else None
+    if var is not None:
+        info = sa.attn_fwd_variant_launch_info(w.B, w.H, w.N, w.d, w.causal, var, w.dtype)
     ws, ws_bytes = None, 0
     if args.workspace:
-        ws_bytes, info = sa.attn_fwd_workspace_bytes(w.B, w.H, w.N, w.d, w.causal, None, w.dtype, w.scale)
+        ws_bytes, info = sa.attn_fwd_workspace_bytes(w.B, w.H, w.N, w.d, w.causal, var, w.dtype)
         ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
 
     def launch(order, stream):
         if ws is not None:
             sa.attn_fwd_workspace(Qd, Kd, Vd, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream,
-                                  workspace=ws)
+                                  workspace=ws, variant=var)
+        elif var is not None:
+            sa.attn_fwd_variant(Qd, Kd, Vd, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream,
+                                variant=var)
         else:
             sa.attn_fwd(Qd, Kd, Vd, O, scale=w.scale, causal=w.causal, scan_order=order, stream=stream)
 
@@ -206,6 +216,9 @@ def main():
                       "tflops_wall": w.flops / (wall_ms * 1e-3) / 1e12}
     head = orders[0]
     r = res[head]
+    traffic, misses, profile = profiled_counters(w.name, bool(ws_bytes)) if var is None else ({}, {}, None)
+    kernel = f"attn_fwd_kernel<d={w.d}, {w.dtype if not ws_bytes else 'f16 copies'}, {'causal' if w.causal else 'full'}, " \
+             f"{info['tile_q'] // 4} rows per wavefront>"
     out = {
         "metric": "attention fwd TFLOP/s (fp16, N=16k, d=128) + L2 miss count, sawtooth vs cyclic",
         "value": r["tflops_wall"],
@@ -221,16 +234,17 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "causal": w.causal,
                    "scan_order": head, "out_dtype": str(o_dtype).replace("torch.", ""), "flops_per_step": w.flops,
-                   "launch": info, "cache_cold_steps": bool(args.evict),
-                   "entry_point": "attn_fwd_workspace" if ws is not None else "attn_fwd", "workspace_bytes": ws_bytes},
+                   "launch": info, "kernel": kernel, "cache_cold_steps": bool(args.evict),
+                   "entry_point": "attn_fwd_workspace" if ws is not None else
+                                  ("attn_fwd_variant" if var is not None else "attn_fwd"),
+                   "workspace_bytes": ws_bytes},
         "roofline": {"bound": "mfma", "achieved": r["tflops"], "peak": MFMA_PEAK_TFLOPS_16BIT,
                      "unit": "TFLOP/s", "frac": r["tflops"] / MFMA_PEAK_TFLOPS_16BIT,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, head, "workspace") if ws_bytes
-                                                           else (args.workload, head)),
-                     "kernel_ms": r["kernel_ms"]},
+                     "traffic": traffic.get(head), "traffic_source": profile,
+                     "kernel_ms": r["kernel_ms"], "kernel": kernel},
         "scan_orders": {o: {"tflops": res[o]["tflops"], "kernel_ms": res[o]["kernel_ms"],
-                            "tcc_miss": MEASURED_TCC_MISS.get((args.workload, o, "workspace") if ws_bytes
-                                                              else (args.workload, o))} for o in orders},
+                            "tcc_miss_profiled": misses.get(o)} for o in orders},
+        "counters_from": profile,
     }
     if not args.no_mfma_probe:
         out["mfma_probe"] = mfma_probe(sa, torch)

@@ -5,7 +5,11 @@
  * HIP device pointer on the current device, every pointer named "host" an ordinary host pointer.
  * No function here throws, aborts, allocates device memory or synchronises the device, unless its
  * comment says otherwise.  All functions return SAWATTN_OK or an error code; the text of the last
- * error on the calling thread is available from sawattn_last_error().
+ * error on the calling thread is available from attn_last_error().
+ *
+ * The four entry points a caller of the method needs are attn_fwd, attn_fwd_launch_info, attn_last_error
+ * and attn_version.  The others serve the studies of the paper's Sec. 3 and Sec. 4.3 (launch variants,
+ * recorded schedules), bfloat16 inputs with caller-provided scratch memory, and older names.
  */
 #ifndef SAWATTN_H
 #define SAWATTN_H
@@ -36,6 +40,14 @@ enum {
     SAWATTN_F32 = 2                /* IEEE binary32; allowed for the output only */
 };
 
+/* The same constants under the short prefix. */
+enum {
+    ATTN_OK = SAWATTN_OK, ATTN_ERR_INVALID_ARG = SAWATTN_ERR_INVALID_ARG,
+    ATTN_ERR_UNSUPPORTED = SAWATTN_ERR_UNSUPPORTED, ATTN_ERR_RUNTIME = SAWATTN_ERR_RUNTIME,
+    ATTN_SCAN_CYCLIC = SAWATTN_SCAN_CYCLIC, ATTN_SCAN_SAWTOOTH = SAWATTN_SCAN_SAWTOOTH,
+    ATTN_F16 = SAWATTN_F16, ATTN_BF16 = SAWATTN_BF16, ATTN_F32 = SAWATTN_F32
+};
+
 /*
  * attn_fwd -- O = softmax(Q K^T * scale) V  (paper Sec. 2.2, Eq. 1), computed tile by tile with an
  * online softmax (Alg. 1) by persistent workgroups (Alg. 2) that scan K/V in `scan_order` (Alg. 4).
@@ -53,7 +65,8 @@ enum {
  *   hip_stream  a hipStream_t (NULL = the default stream).  The kernel is enqueued there and the call
  *            returns without waiting; the caller keeps all buffers alive until the stream has drained.
  *
- * Arithmetic: 16-bit inputs are multiplied exactly and accumulated in fp32 on the matrix cores; the
+ * Arithmetic: 16-bit inputs are multiplied exactly and accumulated in fp32 on the matrix cores; `scale` is
+ * applied to the fp32 scores (no input is rounded again); the
  * running maximum, the running sum and the output accumulator are fp32; the probabilities are
  * rounded to binary16 before the second contraction (for bf16 inputs V is converted to binary16 on
  * the way into LDS, which is exact for |v| in [2^-14, 65504] -- larger bf16 values of V are not
@@ -99,14 +112,12 @@ typedef struct sawattn_variant {
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
                                 0 = default (2).  Ignored by the persistent launch. */
     int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
-                                64 (d = 128 and binary16 inputs only): 256 rows, one workgroup per CU (at most
-                                32 per XCD), every K/V fragment read from LDS feeds two MFMAs, and
-                                scale*log2(e) is folded into Q, rounded to binary16 (a relative error of
-                                2^-11 per element of Q on top of the rounding the inputs already carry: it
-                                grows with the size of the scores; UNSUPPORTED for bfloat16 inputs);
-                                0 = default: 64 for d = 128, binary16 inputs, |scale| <= 2/sqrt(d),
-                                slots_per_domain <= 32 and sequences long enough that every workgroup of an
-                                XCD gets at least one 256-row tile of a head (two under the causal mask):
+                                64 (d = 128 and binary16 inputs only; UNSUPPORTED otherwise): 256 rows, one
+                                workgroup per CU (at most 32 per XCD), every K/V fragment read from LDS feeds
+                                two MFMAs; same arithmetic as the 32-row kernel;
+                                0 = default: 64 for d = 128, binary16 inputs, slots_per_domain <= 32 and
+                                sequences long enough that every workgroup of an XCD gets at least one 256-row
+                                tile of a head (two under the causal mask):
                                 ceil(ceil(N/256) / parts_per_head) >= 32 (64); else 32. */
 } sawattn_variant;
 /*
@@ -124,7 +135,7 @@ typedef struct sawattn_variant {
  *   variant      host, read during the call only; NULL = default.
  *   trace        device, written, or NULL: int32 [grid][max_local_tiles][4] = (b*H + h, query tile
  *                index, first K/V tile visited, last K/V tile visited); grid and max_local_tiles from
- *                attn_fwd_launch_info for the same variant.  Unused records are left untouched.
+ *                attn_fwd_variant_launch_info for the same variant.  Unused records are left untouched.
  *   trace_count  device, written, or NULL (both or neither): int32 [grid], records each workgroup wrote.
  * All other arguments, errors and stream behaviour as attn_fwd; INVALID_ARG for a bad variant field.
  */
@@ -151,13 +162,12 @@ typedef struct sawattn_launch_info {
  * attn_fwd_workspace -- attn_fwd_variant with scratch memory from the caller (paper Sec. 2.2, Alg. 1: the same
  * kernel; the scratch only changes the element type K and V are streamed in).  bfloat16 inputs normally run the
  * 32-rows-per-wavefront kernel, because the faster 64-row kernel needs binary16 operands.  Given a workspace, and
- * where that kernel would be chosen for the same problem in binary16 (d = 128, |scale| <= 2/sqrt(d), sequence long
- * enough; or variant.rows_per_wavefront = 64), the call first writes binary16 copies of K and V into the
- * workspace with one extra kernel on the same stream and then runs the 64-row kernel on them, converting Q as it
- * is loaded.  The copies are exact for bfloat16 magnitudes in [2^-14, 65504] and rounded to binary16 subnormals
- * below (absolute error under 2^-25); larger K or V values are not supported on this path (V has that limit in
- * attn_fwd as well).  In every other case the call is attn_fwd_variant
- * and the workspace is not touched.
+ * where that kernel would be chosen for the same problem in binary16 (d = 128, sequence long enough; or
+ * variant.rows_per_wavefront = 64), the call first writes binary16 copies of K and V into the workspace with one
+ * extra kernel on the same stream and then runs the 64-row kernel on them, converting Q as it is loaded.  The
+ * copies are exact for bfloat16 magnitudes in [2^-14, 65504] and rounded to binary16 subnormals below (absolute
+ * error under 2^-25); larger Q, K or V values are not supported on this path (V has that limit in attn_fwd as
+ * well).  In every other case the call is attn_fwd_variant and the workspace is not touched.
  *
  *   workspace        device, written, 16-byte aligned, must not overlap Q, K, V or O; may be NULL (then this is
  *                    attn_fwd_variant).  Only used during the kernels this call enqueues.
@@ -174,20 +184,28 @@ int attn_fwd_workspace(const void* Q, const void* K, const void* V, void* O,
 /*
  * attn_fwd_workspace_bytes -- how much workspace attn_fwd_workspace would use for a problem: 4*B*H*N*d bytes
  * (binary16 copies of K and V) where the conversion path applies, 0 where it does not (then a workspace changes
- * nothing).  `bytes` and `info` are host memory; `info` may be NULL, else it receives the launch geometry of the
- * kernel attn_fwd_workspace would run.  Validation as attn_fwd_launch_info.  Launches nothing.
+ * nothing).  No passage of the paper corresponds to it: it is the sizing helper of attn_fwd_workspace.  `bytes`
+ * and `info` are host memory; `info` may be NULL, else it receives the launch geometry of the kernel
+ * attn_fwd_workspace would run.  Validation as attn_fwd_variant_launch_info.  Launches nothing.
  */
-int attn_fwd_workspace_bytes(int B, int H, int N, int d, float scale, int causal, int in_dtype,
+int attn_fwd_workspace_bytes(int B, int H, int N, int d, int causal, int in_dtype,
                              const sawattn_variant* variant, size_t* bytes, sawattn_launch_info* info);
 
 /*
- * attn_fwd_launch_info -- report the geometry attn_fwd (variant NULL) or attn_fwd_variant would use
- * (paper Sec. 2.2, Alg. 2 / Alg. 3: grid size and work decode).  `variant` and `out` are host memory.
- * Validates B, H, N, d, scale, in_dtype and the variant like attn_fwd_variant (the input type and the
- * scale take part in the default choice of rows per wavefront).  Launches nothing.
+ * attn_fwd_launch_info -- report the geometry attn_fwd would use (paper Sec. 2.2, Alg. 2: grid size and work
+ * decode; Sec. 3.4: workgroups per cache domain).  `out` is host memory.  Validates B, H, N, d, scan_order and
+ * in_dtype like attn_fwd (the geometry does not depend on the scan order).  Launches nothing.
  */
-int attn_fwd_launch_info(int B, int H, int N, int d, float scale, int causal, int in_dtype,
-                         const sawattn_variant* variant, sawattn_launch_info* out);
+typedef sawattn_launch_info attn_launch_info;
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int scan_order, int in_dtype,
+                         attn_launch_info* out);
+
+/*
+ * attn_fwd_variant_launch_info -- the same for attn_fwd_variant (paper Sec. 2.2, Alg. 2 / Alg. 3); `variant` is
+ * host memory, NULL = the default, and is validated like attn_fwd_variant does.  Launches nothing.
+ */
+int attn_fwd_variant_launch_info(int B, int H, int N, int d, int causal, int in_dtype,
+                                 const sawattn_variant* variant, sawattn_launch_info* out);
 
 /*
  * attn_fwd_plan -- the schedule attn_fwd_variant would run, computed on the host from the same work
@@ -197,32 +215,19 @@ int attn_fwd_launch_info(int B, int H, int N, int d, float scale, int causal, in
  *   trace        host, written: int32 [grid][max_local_tiles][4], same record layout as
  *                attn_fwd_variant; unused records are left untouched.
  *   trace_count  host, written: int32 [grid].
- * B, H, N, d, scale, causal, scan_order, in_dtype and the variant are validated like attn_fwd_variant.
+ * B, H, N, d, causal, scan_order, in_dtype and the variant are validated like attn_fwd_variant.
  */
-int attn_fwd_plan(int B, int H, int N, int d, float scale, int causal, int scan_order, int in_dtype,
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in_dtype,
                   const sawattn_variant* variant, int32_t* trace, int32_t* trace_count);
 
-/*
- * sawattn_mfma_probe -- measurement aid for the roofline (paper Sec. 4.2 / 4.3 report throughput;
- * this gives the matrix rate the chip sustains, next to which the attention rate is read).  Launches
- * one 8-wavefront workgroup per compute unit; each wavefront issues iters*16 v_mfma_f32_32x32x16_f16.
- *
- *   sink       device, >= 512 floats; never written in practice (keeps the work alive).
- *   iters      > 0.
- *   mode       0: all operands zero (no switching in the multipliers: the datasheet condition);
- *              1: operands in registers with values distributed like attention inputs;
- *              2: as 1, with the A operands re-read from an LDS tile with the attention kernel's
- *                 K-operand pattern.  The chip is power limited: 1 and 2 run far below 0.
- *   hip_stream stream to launch on (NULL = default); returns without waiting.
- *   flops_out  host, optional: receives the flop count of the launch (2*32*32*16 per MFMA).
- * Errors: INVALID_ARG, RUNTIME.
- */
-int sawattn_mfma_probe(float* sink, int iters, int mode, void* hip_stream, double* flops_out);
-
 /* Text of the last error raised on the calling thread ("" if none).  Static storage, never NULL. */
-const char* sawattn_last_error(void);
+const char* attn_last_error(void);
 
 /* Library version: major*10000 + minor*100 + patch. */
+int attn_version(void);
+
+/* Older names of the two functions above. */
+const char* sawattn_last_error(void);
 int sawattn_version(void);
 
 #ifdef __cplusplus

@@ -7,7 +7,7 @@ share one L2 (Sec. 3.4); on MI355X that is one XCD, and hardware places workgrou
 w mod 8.  Reading used here (stated in the design notes): the grid-stride loop runs per cache
 domain.
 
-  * B*H heads, ceil(N/T_q) query tiles each.  A head is cut into `parts` interleaved subsets of
+  * B*H heads, ceil(N/tile_q) query tiles each.  A head is cut into `parts` interleaved subsets of
     its tiles (parts = 8 / gcd(B*H, 8)); chunk c = head*parts + part belongs to domain c mod 8 and
     the chunks of a domain are processed in increasing c.
   * The `slots` workgroups of a domain stride over a chunk's tile list with stride `slots`
@@ -19,7 +19,7 @@ domain.
     walking backward into it); N_KV is the number of K/V tiles visible to the query tile.
 
 Variants kept for comparison (same records, other hand-out):
-  * `slots_per_domain`: fewer resident workgroups per domain (Sec. 3.4's sweep over active CTAs).
+  * a smaller `resident`: fewer workgroups per domain (Sec. 3.4's sweep over active CTAs).
   * decode "linear": the printed Alg. 2 -- one list of all (head, tile) pairs, tile fastest;
     persistent workgroup k takes entries k, k+G, k+2G, ... and walks backward on its odd local
     iterations (Alg. 4 as printed).
@@ -28,51 +28,30 @@ Variants kept for comparison (same records, other hand-out):
     numbered chunk after chunk); with two tiles per workgroup the second is walked backward
     under the sawtooth order (Sec. 4.3, the variant that advances the loop by two).
 
-Nothing here is shared with the GPU library.
+The tile height `tile_q` (query rows per workgroup tile) and `resident` (how many workgroups of one domain run
+at the same time, the G of Alg. 2 per domain) are inputs: they are properties of the kernel that runs the
+schedule, not of the method, and the tests take them from the library's launch query or from hand-listed
+cases.  Nothing here is shared with the GPU library.
 """
 from __future__ import annotations
 
 from math import gcd
 
-T_Q, T_KV, DOMAINS = 128, 64, 8
+T_KV, DOMAINS = 64, 8
 
 
 def ceil_div(a: int, b: int) -> int:
     return -(-a // b)
 
 
-def resident_slots(d: int, rows_per_wavefront: int = 32) -> int:
-    """Workgroups of one domain that run at the same time: 32 CUs x 3 per CU at d = 64, x 2 at d = 128,
-    x 1 when a wavefront holds 64 query rows."""
-    if rows_per_wavefront == 64:
-        return 32
-    return 96 if d == 64 else 64
-
-
-def rows_per_wavefront_for(heads: int, N: int, d: int, slots_per_domain: int = 0, causal: bool = False,
-                           dtype: str = "f16", scale: float = None) -> int:
-    """The library's choice when the caller leaves it open: 64 rows per wavefront (256-row tiles) at d = 128
-    with fp16 inputs and |scale| <= 2/sqrt(d) (None: the usual 1/sqrt(d)) if every workgroup of a domain then
-    still gets a tile of a head (two under the causal mask), and the caller did not ask for more
-    workgroups per domain than fit that way."""
-    if d != 128 or dtype != "f16" or slots_per_domain > 32 or (scale is not None and scale * scale * d > 4.0):
-        return 32
-    parts = DOMAINS // gcd(heads, DOMAINS)
-    return 64 if ceil_div(ceil_div(N, 2 * T_Q), parts) >= (64 if causal else 32) else 32
-
-
-def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: str = "domain",
-                    slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128, rows_per_wavefront: int = 0,
-                    causal: bool = False, dtype: str = "f16", scale: float = None):
+def launch_geometry(B: int, H: int, N: int, *, tile_q: int, resident: int, launch: str = "persistent",
+                    decode: str = "domain", tiles_per_workgroup: int = 2):
     heads = B * H
-    rows = rows_per_wavefront or rows_per_wavefront_for(heads, N, d, slots_per_domain, causal, dtype, scale)
-    tile_q = T_Q * rows // 32
-    slots_per_domain = slots_per_domain or resident_slots(d, rows)
     q_tiles = ceil_div(N, tile_q)
     total = heads * q_tiles
     if decode == "linear":
         if launch == "persistent":
-            slots = min(ceil_div(total, DOMAINS), slots_per_domain)
+            slots = min(ceil_div(total, DOMAINS), resident)
             local = ceil_div(total, DOMAINS * slots)
         else:
             slots = ceil_div(ceil_div(total, tiles_per_workgroup), DOMAINS)
@@ -83,7 +62,7 @@ def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: 
     largest_part = ceil_div(q_tiles, parts)
     chunks_per_domain = heads * parts // DOMAINS
     if launch == "persistent":
-        slots = min(largest_part, slots_per_domain)
+        slots = min(largest_part, resident)
         rounds = ceil_div(largest_part, slots)
         return {"grid": DOMAINS * slots, "slots": slots, "parts": parts, "q_tiles": q_tiles,
                 "rounds_per_chunk": rounds, "chunks_per_domain": chunks_per_domain,
@@ -95,7 +74,7 @@ def launch_geometry(B: int, H: int, N: int, launch: str = "persistent", decode: 
             "tile_q": tile_q}
 
 
-def visible_kv(t: int, N: int, causal: bool, tile_q: int = T_Q) -> int:
+def visible_kv(t: int, N: int, causal: bool, tile_q: int) -> int:
     """Number of K/V tiles query tile t (of tile_q rows) has to visit."""
     if not causal:
         return ceil_div(N, T_KV)
@@ -103,18 +82,17 @@ def visible_kv(t: int, N: int, causal: bool, tile_q: int = T_Q) -> int:
     return ceil_div(last_row, T_KV)
 
 
-def record(head: int, t: int, N: int, causal: bool, backward: bool, tile_q: int = T_Q):
+def record(head: int, t: int, N: int, causal: bool, backward: bool, tile_q: int):
     n_kv = visible_kv(t, N, causal, tile_q)
     return (head, t, n_kv - 1, 0) if backward else (head, t, 0, n_kv - 1)
 
 
-def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, launch: str = "persistent",
-             decode: str = "domain", slots_per_domain: int = 0, tiles_per_workgroup: int = 2, d: int = 128,
-             rows_per_wavefront: int = 0, dtype: str = "f16", scale: float = None):
+def schedule(B: int, H: int, N: int, causal: bool, scan_order: str, *, tile_q: int, resident: int,
+             launch: str = "persistent", decode: str = "domain", tiles_per_workgroup: int = 2):
     """Return {workgroup: [(head, query tile, first K/V tile, last K/V tile), ...]} in the order
     each workgroup processes its tiles."""
-    geo = launch_geometry(B, H, N, launch, decode, slots_per_domain, tiles_per_workgroup, d, rows_per_wavefront,
-                          causal, dtype, scale)
+    geo = launch_geometry(B, H, N, tile_q=tile_q, resident=resident, launch=launch, decode=decode,
+                          tiles_per_workgroup=tiles_per_workgroup)
     heads, parts, slots, grid, tq = B * H, geo["parts"], geo["slots"], geo["grid"], geo["tile_q"]
     saw = scan_order == "sawtooth"
     out = {}

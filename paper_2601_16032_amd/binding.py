@@ -6,12 +6,11 @@ library has not been built, loading raises.  PyTorch is used for device memory a
 from __future__ import annotations
 
 import ctypes
-import math
 import os
 
 import torch
 
-from .build import LIB_PATH
+from .build import LIB_PATH, PROBE_LIB_PATH
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_RUNTIME = 0, 1, 2, 3
 SCAN_CYCLIC, SCAN_SAWTOOTH = 0, 1
@@ -81,70 +80,99 @@ def lib() -> ctypes.CDLL:
         L.attn_fwd_workspace.restype = ci
         L.attn_fwd_workspace.argtypes = L.attn_fwd_variant.argtypes + [vp, ctypes.c_size_t]
         L.attn_fwd_workspace_bytes.restype = ci
-        L.attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, pv, ctypes.POINTER(ctypes.c_size_t),
+        L.attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, pv, ctypes.POINTER(ctypes.c_size_t),
                                                ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_launch_info.restype = ci
-        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, pv, ctypes.POINTER(LaunchInfo)]
+        L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(LaunchInfo)]
+        L.attn_fwd_variant_launch_info.restype = ci
+        L.attn_fwd_variant_launch_info.argtypes = [ci, ci, ci, ci, ci, ci, pv, ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_plan.restype = ci
-        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ctypes.c_float, ci, ci, ci, pv, vp, vp]
-        L.sawattn_mfma_probe.restype = ci
-        L.sawattn_mfma_probe.argtypes = [vp, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
-        L.sawattn_last_error.restype = ctypes.c_char_p
-        L.sawattn_last_error.argtypes = []
-        L.sawattn_version.restype = ci
-        L.sawattn_version.argtypes = []
+        L.attn_fwd_plan.argtypes = [ci, ci, ci, ci, ci, ci, ci, pv, vp, vp]
+        for name in ("attn_last_error", "sawattn_last_error"):
+            getattr(L, name).restype = ctypes.c_char_p
+            getattr(L, name).argtypes = []
+        for name in ("attn_version", "sawattn_version"):
+            getattr(L, name).restype = ci
+            getattr(L, name).argtypes = []
         _lib = L
     return _lib
 
 
-def sawattn_last_error() -> str:
-    return lib().sawattn_last_error().decode()
+_probe_lib = None
 
 
-def sawattn_version() -> int:
-    return int(lib().sawattn_version())
+def probe_lib() -> ctypes.CDLL:
+    """Load libsawattn_probe.so, the benchmark's matrix-rate probe (built with the main library)."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise FileNotFoundError(f"{PROBE_LIB_PATH} is not built; run `python -m paper_2601_16032_amd.build` first")
+        L = ctypes.CDLL(PROBE_LIB_PATH)
+        L.sawattn_mfma_probe.restype = ctypes.c_int
+        L.sawattn_mfma_probe.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.POINTER(ctypes.c_double)]
+        L.sawattn_probe_last_error.restype = ctypes.c_char_p
+        L.sawattn_probe_last_error.argtypes = []
+        _probe_lib = L
+    return _probe_lib
+
+
+def attn_last_error() -> str:
+    return lib().attn_last_error().decode()
+
+
+def attn_version() -> int:
+    return int(lib().attn_version())
+
+
+sawattn_last_error, sawattn_version = attn_last_error, attn_version   # older names
 
 
 def _check(rc: int):
     if rc != OK:
-        raise SawattnError(rc, sawattn_last_error())
+        raise SawattnError(rc, attn_last_error())
 
 
 def _in_dtype_code(dtype) -> int:
     return {"f16": F16, "bf16": BF16}.get(dtype, _DTYPE_CODE.get(dtype, dtype))
 
 
-def _scale_or_usual(scale, d: int) -> float:
-    return float(scale) if scale is not None else 1.0 / math.sqrt(d)
-
-
-def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False, variant: Variant = None,
-                         dtype="f16", scale: float = None) -> dict:
-    """`scale` = None stands for the usual 1/sqrt(d)."""
+def attn_fwd_launch_info(B: int, H: int, N: int, d: int, causal: bool = False, scan_order="sawtooth",
+                         dtype="f16") -> dict:
+    """Launch geometry of attn_fwd."""
     info = LaunchInfo()
-    _check(lib().attn_fwd_launch_info(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _in_dtype_code(dtype),
-                                      _vptr(variant), ctypes.byref(info)))
+    _check(lib().attn_fwd_launch_info(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order], _in_dtype_code(dtype),
+                                      ctypes.byref(info)))
+    return info.as_dict()
+
+
+def attn_fwd_variant_launch_info(B: int, H: int, N: int, d: int, causal: bool = False, variant: Variant = None,
+                                 dtype="f16") -> dict:
+    """Launch geometry of attn_fwd_variant (variant None: the default, as attn_fwd_launch_info)."""
+    info = LaunchInfo()
+    _check(lib().attn_fwd_variant_launch_info(B, H, N, d, int(bool(causal)), _in_dtype_code(dtype), _vptr(variant),
+                                              ctypes.byref(info)))
     return info.as_dict()
 
 
 def attn_fwd_plan(B: int, H: int, N: int, d: int, causal: bool = False, scan_order="sawtooth",
-                  variant: Variant = None, dtype="f16", scale: float = None):
+                  variant: Variant = None, dtype="f16"):
     """Host-side schedule: returns (trace[grid, max_local, 4], count[grid]) as CPU int32 tensors."""
-    info = attn_fwd_launch_info(B, H, N, d, causal, variant, dtype, scale)
+    info = attn_fwd_variant_launch_info(B, H, N, d, causal, variant, dtype)
     trace = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32)
     count = torch.zeros((info["grid"],), dtype=torch.int32)
-    _check(lib().attn_fwd_plan(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _SCAN_CODE[scan_order],
-                               _in_dtype_code(dtype), _vptr(variant), trace.data_ptr(), count.data_ptr()))
+    _check(lib().attn_fwd_plan(B, H, N, d, int(bool(causal)), _SCAN_CODE[scan_order], _in_dtype_code(dtype),
+                               _vptr(variant), trace.data_ptr(), count.data_ptr()))
     return trace, count
 
 
 def attn_fwd_workspace_bytes(B: int, H: int, N: int, d: int, causal: bool = False, variant: Variant = None,
-                             dtype="bf16", scale: float = None):
+                             dtype="bf16"):
     """(bytes of workspace attn_fwd_workspace would use -- 0 where it changes nothing --, launch geometry)."""
     n = ctypes.c_size_t(0)
     info = LaunchInfo()
-    _check(lib().attn_fwd_workspace_bytes(B, H, N, d, _scale_or_usual(scale, d), int(bool(causal)), _in_dtype_code(dtype),
-                                          _vptr(variant), ctypes.byref(n), ctypes.byref(info)))
+    _check(lib().attn_fwd_workspace_bytes(B, H, N, d, int(bool(causal)), _in_dtype_code(dtype), _vptr(variant),
+                                          ctypes.byref(n), ctypes.byref(info)))
     return int(n.value), info.as_dict()
 
 
@@ -153,7 +181,10 @@ def sawattn_mfma_probe(iters: int, mode: int, stream=None) -> float:
     sink = torch.zeros(512, dtype=torch.float32, device="cuda")
     flops = ctypes.c_double(0.0)
     st = stream if stream is not None else torch.cuda.current_stream()
-    _check(lib().sawattn_mfma_probe(sink.data_ptr(), int(iters), int(mode), st.cuda_stream, ctypes.byref(flops)))
+    L = probe_lib()
+    rc = L.sawattn_mfma_probe(sink.data_ptr(), int(iters), int(mode), st.cuda_stream, ctypes.byref(flops))
+    if rc != OK:
+        raise SawattnError(rc, L.sawattn_probe_last_error().decode())
     return float(flops.value)
 
 
@@ -192,7 +223,7 @@ def attn_fwd_variant(Q, K, V, O=None, *, scale: float, causal: bool = False, sca
     B, H, N, d = Q.shape
     tr = cnt = None
     if trace:
-        info = attn_fwd_launch_info(B, H, N, d, causal, variant, Q.dtype, scale)
+        info = attn_fwd_variant_launch_info(B, H, N, d, causal, variant, Q.dtype)
         tr = torch.full((info["grid"], max(info["max_local_tiles"], 1), 4), -1, dtype=torch.int32,
                         device=Q.device)
         cnt = torch.zeros((info["grid"],), dtype=torch.int32, device=Q.device)
@@ -210,7 +241,7 @@ def attn_fwd_workspace(Q, K, V, O=None, *, scale: float, causal: bool = False, s
     here when None and needed).  Returns like attn_fwd_variant."""
     O = _marshal(Q, K, V, O, o_dtype)
     B, H, N, d = Q.shape
-    need, info = attn_fwd_workspace_bytes(B, H, N, d, causal, variant, Q.dtype, scale)
+    need, info = attn_fwd_workspace_bytes(B, H, N, d, causal, variant, Q.dtype)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     tr = cnt = None

@@ -73,6 +73,7 @@ struct Params {
     int q_bf16;            // wide variant on converted inputs: Q is still bfloat16 (K and V are binary16 copies)
     int max_local;
     float c;               // |scale| * log2(e): scores are handled in the log2 domain
+    float thr;             // wide variant: the rescale slack in units of the raw score, kRescaleSlack / c
     Schedule sched;
 };
 
@@ -308,8 +309,10 @@ __device__ __forceinline__ void mfma_s(f16v& acc, u4 k_frag, const u4& q_frag) {
     else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
 }
 // First MFMA of an S^T block whose accumulator starts from the register block `init`.
+template <bool BF16>
 __device__ __forceinline__ void mfma_s_init(f16v& acc, u4 k_frag, const u4& q_frag, const f16v& init) {
-    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3" : "=&v"(acc) : "v"(k_frag), "a"(q_frag), "v"(init));
+    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(k_frag), "a"(q_frag), "v"(init));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3" : "=&v"(acc) : "v"(k_frag), "a"(q_frag), "v"(init));
 }
 __device__ __forceinline__ void mfma_o(f16v& acc, s8 v_frag, const u4& p_frag) {
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_frag), "v"(p_frag));
@@ -342,8 +345,8 @@ __device__ __forceinline__ void mfma_guard(f16v (&acc)[NACC]) {
 // WIDE: the tile state is the wide variant's -- Q^T fragments and O^T accumulators live in accumulation
 // registers and the MFMAs are the written-out ones.
 template <int D, bool BF16, bool CAUSAL, bool MASKED, bool WIDE = false>
-__device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>& ra, float c, int kv0, int qrow, int lane,
-                                             int N) {
+__device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>& ra, float c, float thr, int kv0, int qrow,
+                                             int lane, int N) {
     using G = Geo<D>;
     constexpr int KS = D / 16, DB = D / 32;
     const int g = lane >> 5;
@@ -399,10 +402,12 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
     mx = pair_max(mx);
-    const float tmax = mx * c;
-    if (__builtin_amdgcn_ballot_w64(tmax > st.M + kRescaleSlack) != 0) {
+    // The wide variant keeps its reference maximum in units of the raw score (its pipelined loop lets the
+    // MFMAs start from -M); the other kernels keep it in the log2 domain.
+    const float tmax = WIDE ? mx : mx * c;
+    if (__builtin_amdgcn_ballot_w64(tmax > st.M + (WIDE ? thr : kRescaleSlack)) != 0) {
         const float Mnew = fmaxf(st.M, tmax);
-        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st.M - Mnew);
+        const float alpha = (st.M == -INFINITY) ? 1.0f : fast_exp2(WIDE ? c * (st.M - Mnew) : st.M - Mnew);
         st.M = Mnew;
         st.L *= alpha;
 #pragma unroll
@@ -422,8 +427,8 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int r = 8 * h + 2 * i;
-                float x0 = fast_exp2(__builtin_fmaf(s[b][r], c, -Mref));
-                float x1 = fast_exp2(__builtin_fmaf(s[b][r + 1], c, -Mref));
+                float x0 = fast_exp2(WIDE ? c * (s[b][r] - Mref) : __builtin_fmaf(s[b][r], c, -Mref));
+                float x1 = fast_exp2(WIDE ? c * (s[b][r + 1] - Mref) : __builtin_fmaf(s[b][r + 1], c, -Mref));
                 if constexpr (MASKED) {
                     if ((masked >> (16 * b + r)) & 1u) x0 = 0.f;
                     if ((masked >> (16 * b + r + 1)) & 1u) x1 = 0.f;
@@ -469,7 +474,7 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 // and, while computing, fetches the tile of iteration it+1 into the other pair.
 template <int D, bool BF16, bool CAUSAL, bool MASKED, int NH>
 __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const LaneMap<D>& lm, const char* Kh, const char* Vh, int N,
-                                              float c, int j_first, int step, int count, int qw0, int qrow, int lane,
+                                              float c, float thr, int j_first, int step, int count, int qw0, int qrow, int lane,
                                               LDS_PTR(char) lds) {
     using G = Geo<D>;
     if (count <= 0) return;
@@ -510,7 +515,7 @@ __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const Lane
 #pragma unroll
         for (int h = 0; h < NH; ++h) {   // half h: query rows qw0 + 32h .. +31 (this lane: qrow + 32h)
             const bool active = qw0 + 32 * h < N && (!CAUSAL || kv0 <= qw0 + 32 * h + 31);
-            if (active) compute_tile<D, BF16, CAUSAL, MASKED, NH == 2>(st[h], ra, c, kv0, qrow + 32 * h, lane, N);
+            if (active) compute_tile<D, BF16, CAUSAL, MASKED, NH == 2>(st[h], ra, c, thr, kv0, qrow + 32 * h, lane, N);
         }
         ra.flip(cur ? -G::kTile : G::kTile);
         if (more) {
@@ -807,8 +812,9 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
 constexpr int kWideBuffers = 4;
 constexpr int kWideLdsBytes = 2 * kWideBuffers * Geo<128>::kTile;
 
+template <bool BF16>
 __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], const LaneMap<128>& lm, const char* Kh,
-                                                     const char* Vh, int j_first, int step, int count,
+                                                     const char* Vh, float c, float thr, int j_first, int step, int count,
                                                      LDS_PTR(char) lds) {
     constexpr int D = 128;
     using G = Geo<D>;
@@ -854,8 +860,9 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     // Softmax work items of half h, pair u = 0..15: the two exponentials, the convert into the B operand,
     // the addition to the running sum.
     auto exp2_pair = [&](int h, int u) {
-        e0[h][u] = fast_exp2(S[h][u / 8][2 * (u % 8)]);
-        e1[h][u] = fast_exp2(S[h][u / 8][2 * (u % 8) + 1]);
+        const float x0 = c * S[h][u / 8][2 * (u % 8)], x1 = c * S[h][u / 8][2 * (u % 8) + 1];
+        e0[h][u] = fast_exp2(x0);
+        e1[h][u] = fast_exp2(x1);
     };
     auto convert_pair = [&](int h, int u) {
         pf[h][u / 4][u % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(f2{e0[h][u], e1[h][u]}, h2));
@@ -896,8 +903,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             if (m + RA < NA) a[m + RA] = k0_read(m + RA);
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (m < 2) mfma_s_first<false>(S[h][m & 1], a[m], st[h].qf[m / 2]);
-                else mfma_s<false>(S[h][m & 1], a[m], st[h].qf[m / 2]);
+                if (m < 2) mfma_s_first<BF16>(S[h][m & 1], a[m], st[h].qf[m / 2]);
+                else mfma_s<BF16>(S[h][m & 1], a[m], st[h].qf[m / 2]);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -913,11 +920,11 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, S[h][r >> 4][r & 15]), S[h][r >> 4][(r & 15) + 1]);
             const float tmax = pair_max(mx);
             // the first tile of a query tile finds M = -inf and takes its own maximum as the reference
-            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + kRescaleSlack)) != 0) {
+            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + thr)) != 0) {
                 st[h].L += L_hi[h];
                 L_hi[h] = 0.f;
                 const float Mnew = fmaxf(st[h].M, tmax);
-                const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st[h].M - Mnew);
+                const float alpha = (st[h].M == -INFINITY) ? 1.0f : fast_exp2(c * (st[h].M - Mnew));
                 st[h].M = Mnew;
                 st[h].L *= alpha;
 #pragma unroll
@@ -967,8 +974,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const int t = 2 * q + h;
-                    if (q % 8 == 0) mfma_s_init(S[h][b], a[n], st[h].qf[ks], negM[h]);   // the block's first MFMA
-                    else mfma_s<false>(S[h][b], a[n], st[h].qf[ks]);
+                    if (q % 8 == 0) mfma_s_init<BF16>(S[h][b], a[n], st[h].qf[ks], negM[h]);   // the block's first MFMA
+                    else mfma_s<BF16>(S[h][b], a[n], st[h].qf[ks]);
                     if (t < 16) {
                         // exponentials of the second block of tile i: pair 8 + t/2 of half t%2, convert of the one before
                         const int hh = t & 1, u = 8 + t / 2;
@@ -1041,7 +1048,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                 if (t == 10) {
                     tmax_ahead[0] = mx[0];
                     tmax_ahead[1] = mx[1];
-                    need = __builtin_amdgcn_ballot_w64(!(mx[0] <= kRescaleSlack) || !(mx[1] <= kRescaleSlack)) != 0;
+                    need = __builtin_amdgcn_ballot_w64(!(mx[0] <= thr) || !(mx[1] <= thr)) != 0;
                 }
                 if (t >= 10 && t < 18) {            // pairs 0..3 of both halves: pf[.][0]
                     const int hh = t & 1, u = (t - 10) / 2;
@@ -1082,9 +1089,9 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             float t = tmax_ahead[h];
             asm volatile("" : "+v"(t));
             t = pair_max(t);     // the two lanes of a query row move together
-            if (__builtin_amdgcn_ballot_w64(!(t <= kRescaleSlack)) != 0) {
+            if (__builtin_amdgcn_ballot_w64(!(t <= thr)) != 0) {
                 const float up = fmaxf(t, 0.f);
-                const float alpha = fast_exp2(-up);
+                const float alpha = fast_exp2(-c * up);
                 st[h].M += up;
                 st[h].L = (st[h].L + L_hi[h]) * alpha;
                 L_hi[h] = 0.f;
@@ -1172,19 +1179,7 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
             v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
             if constexpr (NH == 2) {
-                // the wide variant folds scale*log2(e) into Q (one rounding to binary16 per element)
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const unsigned word = v[w];   // (a copy: bit casts of a vector element do not read that element)
-                    f2 x;
-                    if (p.q_bf16) {
-                        x[0] = __builtin_bit_cast(float, word << 16);
-                        x[1] = __builtin_bit_cast(float, word & 0xffff0000u);
-                    } else {
-                        x = __builtin_convertvector(__builtin_bit_cast(h2, word), f2);
-                    }
-                    v[w] = __builtin_bit_cast(unsigned, __builtin_convertvector(x * p.c, h2));
-                }
+                if (p.q_bf16) v = bf16x8_to_f16x8(v);   // K and V are binary16 copies: Q follows (exact for normal binary16 magnitudes)
                 asm volatile("" : "=a"(st[h].qf[ks]) : "0"(v));   // accumulation registers from here on
             } else {
                 st[h].qf[ks] = v;
@@ -1197,7 +1192,7 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         st[h].M = -INFINITY;
         st[h].L = 0.f;
     }
-    const float c = NH == 2 ? 1.0f : p.c;   // (the wide variant's Q carries the factor)
+    const float c = p.c, thr = p.thr;
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
     // the tiles that reach past the first row of this query tile.  They sit at one end of the scan,
@@ -1215,17 +1210,17 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             int l2 = lane;
             asm volatile("" : "+v"(l2));
             const LaneMap<D> lm2(wave, l2);
-            pipelined_range_wide(st, lm2, Kh, Vh, j_first, step, n_plain, lds);
+            pipelined_range_wide<BF16>(st, lm2, Kh, Vh, c, thr, j_first, step, n_plain, lds);
         }
     };
     auto masked = [&](int j_first) {
         if constexpr (NH == 1) {
-            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, lane, lds);
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, thr, j_first, step, n_masked, qw0, qrow, lane, lds);
         } else {
             int l2 = lane;
             asm volatile("" : "+v"(l2));
             const LaneMap<D> lm2(wave, l2);
-            general_range<D, BF16, CAUSAL, true, NH>(st, lm2, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, l2, lds);
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm2, Kh, Vh, N, c, thr, j_first, step, n_masked, qw0, qrow, l2, lds);
         }
     };
     if (step > 0) {
@@ -1337,77 +1332,6 @@ __global__ __launch_bounds__(kThreads, NH == 2 ? 1 : (D == 64 ? 3 : 2)) void att
 }
 
 
-// ------------------------------------------------------------------------------- sustained-rate probe
-// What the matrix pipes of this chip sustain, to put the datasheet peak into context: every
-// wavefront runs `iters` x 16 v_mfma_f32_32x32x16_f16 on four independent accumulators.
-//   mode 0: all operands zero.  Nothing switches in the multipliers, the chip holds its peak clock
-//           and the rate is the datasheet's.
-//   mode 1: operands in registers holding values distributed like attention inputs (about
-//           0.5 x standard normal); A cycles through four registers, B through four.
-//   mode 2: as mode 1 with the A operands re-read from an LDS tile with the K-operand access
-//           pattern of the attention kernel, one ds_read_b128 per MFMA.
-// The chip is power limited and lowers its clock with switching activity, so the rate with live
-// data is far below the rate with zeros, whatever the instruction stream does besides.
-__device__ __forceinline__ unsigned probe_hash(unsigned x) {
-    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
-    return x;
-}
-// Two binary16 values, each about 0.5 x standard normal (sum of four uniforms, centred and scaled).
-__device__ __forceinline__ unsigned probe_pair(unsigned seed) {
-    h2 v;
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const unsigned r = probe_hash(seed * 2u + k + 1u);
-        const float u = (float)(r & 255u) + (float)((r >> 8) & 255u) + (float)((r >> 16) & 255u) + (float)(r >> 24);
-        v[k] = (_Float16)((u - 510.0f) * (0.5f / 147.8f));
-    }
-    return __builtin_bit_cast(unsigned, v);
-}
-
-__global__ __launch_bounds__(512) void mfma_probe_kernel(float* sink, int iters, int mode) {
-    __shared__ __align__(16) char tile[16384];
-    LDS_PTR(char) lds = (LDS_PTR(char))tile;
-    for (int i = threadIdx.x; i < 16384 / 4; i += blockDim.x) ((LDS_PTR(unsigned))lds)[i] = probe_pair(i);
-    __syncthreads();
-    const int lane = threadIdx.x & 63, g = lane >> 5, ln = lane & 31;
-    u4 a4[4], b4[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            a4[q][e] = mode == 0 ? 0u : probe_pair(100000u + threadIdx.x * 32u + q * 4u + e);
-            b4[q][e] = mode == 0 ? 0u : probe_pair(900000u + threadIdx.x * 32u + q * 4u + e);
-        }
-    f16v c[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) c[q][r] = 0.f;
-    unsigned addr[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) addr[ks] = (unsigned)(size_t)lds + ln * 256 + ((2 * ks + g) ^ Geo<128>::swz(ln)) * 16;
-    if (mode != 2) {
-        for (int i = 0; i < iters; ++i) {
-#pragma unroll
-            for (int t = 0; t < 16; ++t) c[t & 3] = mfma_16bit<false>(a4[t & 3], b4[(t >> 2) & 3], c[t & 3]);
-        }
-    } else {
-        for (int i = 0; i < iters; ++i) {
-            u4 a[16];
-            a[0] = *(LDS_PTR(u4))(size_t)addr[0];
-            a[1] = *(LDS_PTR(u4))(size_t)(addr[0] + 8192);
-#pragma unroll
-            for (int t = 0; t < 16; ++t) {
-                if (t + 2 < 16) a[t + 2] = *(LDS_PTR(u4))(size_t)(addr[(t + 2) / 2] + ((t + 2) & 1) * 8192);
-                c[t & 3] = mfma_16bit<false>(a[t], b4[(t >> 2) & 3], c[t & 3]);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    }
-    const float res = c[0][0] + c[1][1] + c[2][2] + c[3][3];
-    if (res == 123.456f) sink[threadIdx.x] = res;   // never true: keeps the accumulators alive
-}
-
 // ------------------------------------------------------------------------------------------- host
 
 thread_local char g_err[256] = "";
@@ -1466,7 +1390,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 }
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
-int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, float scale, const sawattn_variant* v, Schedule* out) {
+int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out) {
     int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
@@ -1478,7 +1402,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, float scale
         if (v->rows_per_wavefront == 64 && (d != 128 || bf16))
             return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128 and binary16 inputs");
         rows = v->rows_per_wavefront;
-        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16, scale);
+        if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16);
         if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : kTileQ))
             return fail(SAWATTN_ERR_INVALID_ARG,
                         "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per wavefront)");
@@ -1489,7 +1413,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, float scale
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
     }
-    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16, scale);
+    if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
     const int tile_q = rows == 64 ? 2 * kTileQ : kTileQ;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q);
@@ -1497,12 +1421,12 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, float scale
 }
 
 // Whether bfloat16 inputs, converted to binary16, would run the wide variant: then a workspace pays.
-int workspace_schedule(int B, int H, int N, int d, bool causal, bool bf16, float scale, const sawattn_variant* v,
-                       Schedule* out, bool* use) {
+int workspace_schedule(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out,
+                       bool* use) {
     *use = false;
     if (!bf16 || d != 128) return SAWATTN_OK;
     Schedule s;
-    const int rc = schedule_for(B, H, N, d, causal, false, scale, v, &s);
+    const int rc = schedule_for(B, H, N, d, causal, false, v, &s);
     if (rc != SAWATTN_OK) return rc;
     if (s.tile_q > kTileQ) { *use = true; *out = s; }
     return SAWATTN_OK;
@@ -1528,11 +1452,11 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     Schedule sched;
     bool converted = false;   // bfloat16 inputs through binary16 copies of K and V in the caller's workspace
     if (workspace) {
-        rc = workspace_schedule(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &sched, &converted);
+        rc = workspace_schedule(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &sched, &converted);
         if (rc != SAWATTN_OK) return rc;
     }
     if (!converted) {
-        rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &sched);
+        rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &sched);
         if (rc != SAWATTN_OK) return rc;
     }
     {   // A workgroup writes its O rows while others still read Q, K, V: O may not share memory with them.
@@ -1565,6 +1489,7 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.negate_q = scale < 0.f;
     p.q_bf16 = converted;
     p.c = (float)(std::fabs((double)scale) * 1.4426950408889634074);
+    p.thr = p.c > 0.f ? std::min(kRescaleSlack / p.c, 1e30f) : 1e30f;
     p.sched = sched;
     p.max_local = sched.local_iters;
     const int grid = sched.grid;
@@ -1593,6 +1518,13 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     return ca ? launch<64, false, true, 1>(p, grid, stream) : launch<64, false, false, 1>(p, grid, stream);
 }
 
+// Argument checks shared by the queries that launch nothing.
+int check_query(int B, int H, int N, int d, int in_dtype) {
+    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
+        return fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
+    return check_shape(B, H, N, d);
+}
+
 }  // namespace sawattn
 
 extern "C" {
@@ -1618,21 +1550,18 @@ int attn_fwd_workspace(const void* Q, const void* K, const void* V, void* O, int
                         trace_count, workspace, workspace_bytes);
 }
 
-int attn_fwd_workspace_bytes(int B, int H, int N, int d, float scale, int causal, int in_dtype,
-                             const sawattn_variant* variant, size_t* bytes, sawattn_launch_info* info) {
+int attn_fwd_workspace_bytes(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,
+                             size_t* bytes, sawattn_launch_info* info) {
     using namespace sawattn;
     if (!bytes) return fail(SAWATTN_ERR_INVALID_ARG, "bytes must be non-null");
-    if (!std::isfinite(scale)) return fail(SAWATTN_ERR_INVALID_ARG, "scale must be finite");
-    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
-        return fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
-    int rc = check_shape(B, H, N, d);
+    int rc = check_query(B, H, N, d, in_dtype);
     if (rc != SAWATTN_OK) return rc;
     Schedule s;
     bool use = false;
-    rc = workspace_schedule(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s, &use);
+    rc = workspace_schedule(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s, &use);
     if (rc != SAWATTN_OK) return rc;
     if (!use) {
-        rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s);
+        rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
         if (rc != SAWATTN_OK) return rc;
     }
     *bytes = use ? (size_t)B * H * N * d * 4 : 0;
@@ -1640,34 +1569,35 @@ int attn_fwd_workspace_bytes(int B, int H, int N, int d, float scale, int causal
     return SAWATTN_OK;
 }
 
-int attn_fwd_launch_info(int B, int H, int N, int d, float scale, int causal, int in_dtype,
-                         const sawattn_variant* variant, sawattn_launch_info* out) {
-    if (!out) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "out must be non-null");
-    if (!std::isfinite(scale)) return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "scale must be finite");
-    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
-        return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
-    int rc = sawattn::check_shape(B, H, N, d);
+int attn_fwd_variant_launch_info(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,
+                                 sawattn_launch_info* out) {
+    using namespace sawattn;
+    if (!out) return fail(SAWATTN_ERR_INVALID_ARG, "out must be non-null");
+    int rc = check_query(B, H, N, d, in_dtype);
     if (rc != SAWATTN_OK) return rc;
-    sawattn::Schedule s;
-    rc = sawattn::schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s);
+    Schedule s;
+    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
     if (rc != SAWATTN_OK) return rc;
-    sawattn::fill_info(s, d, out);
+    fill_info(s, d, out);
     return SAWATTN_OK;
 }
 
-int attn_fwd_plan(int B, int H, int N, int d, float scale, int causal, int scan_order, int in_dtype,
-                  const sawattn_variant* variant, int32_t* trace, int32_t* trace_count) {
+int attn_fwd_launch_info(int B, int H, int N, int d, int causal, int scan_order, int in_dtype, sawattn_launch_info* out) {
+    if (scan_order != SAWATTN_SCAN_CYCLIC && scan_order != SAWATTN_SCAN_SAWTOOTH)
+        return sawattn::fail(SAWATTN_ERR_INVALID_ARG, "scan_order must be SAWATTN_SCAN_CYCLIC or SAWATTN_SCAN_SAWTOOTH");
+    return attn_fwd_variant_launch_info(B, H, N, d, causal, in_dtype, nullptr, out);
+}
+
+int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in_dtype, const sawattn_variant* variant,
+                  int32_t* trace, int32_t* trace_count) {
     using namespace sawattn;
     if (!trace || !trace_count) return fail(SAWATTN_ERR_INVALID_ARG, "trace and trace_count must be non-null");
-    if (!std::isfinite(scale)) return fail(SAWATTN_ERR_INVALID_ARG, "scale must be finite");
-    if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
-        return fail(SAWATTN_ERR_INVALID_ARG, "in_dtype must be SAWATTN_F16 or SAWATTN_BF16");
     if (scan_order != SAWATTN_SCAN_CYCLIC && scan_order != SAWATTN_SCAN_SAWTOOTH)
         return fail(SAWATTN_ERR_INVALID_ARG, "scan_order must be SAWATTN_SCAN_CYCLIC or SAWATTN_SCAN_SAWTOOTH");
-    int rc = check_shape(B, H, N, d);
+    int rc = check_query(B, H, N, d, in_dtype);
     if (rc != SAWATTN_OK) return rc;
     Schedule s;
-    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, scale, variant, &s);
+    rc = schedule_for(B, H, N, d, causal != 0, in_dtype == SAWATTN_BF16, variant, &s);
     if (rc != SAWATTN_OK) return rc;
     // the kernel's outer loop, one workgroup at a time
     for (int wg = 0; wg < s.grid; ++wg) {
@@ -1685,22 +1615,9 @@ int attn_fwd_plan(int B, int H, int N, int d, float scale, int causal, int scan_
     return SAWATTN_OK;
 }
 
-int sawattn_mfma_probe(float* sink, int iters, int mode, void* hip_stream, double* flops_out) {
-    using namespace sawattn;
-    if (!sink || iters <= 0 || mode < 0 || mode > 2) return fail(SAWATTN_ERR_INVALID_ARG, "sink non-null, iters > 0, mode 0, 1 or 2");
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(SAWATTN_ERR_RUNTIME, "cannot query the device");
-    }
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(cus), dim3(512), 0, static_cast<hipStream_t>(hip_stream), sink, iters, mode);
-    if (hipGetLastError() != hipSuccess) return fail(SAWATTN_ERR_RUNTIME, "probe launch failed");
-    if (flops_out) *flops_out = (double)cus * 8.0 * (double)iters * 16.0 * (2.0 * 32 * 32 * 16);
-    return SAWATTN_OK;
-}
-
-const char* sawattn_last_error(void) { return sawattn::g_err; }
-
-int sawattn_version(void) { return 100; }
+const char* attn_last_error(void) { return sawattn::g_err; }
+int attn_version(void) { return 200; }
+const char* sawattn_last_error(void) { return attn_last_error(); }
+int sawattn_version(void) { return attn_version(); }
 
 }  // extern "C"

@@ -45,12 +45,9 @@ SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b);
 // workgroup tiles) for head dimension 128 and binary16 inputs once the steady state dominates, i.e.
 // every resident workgroup of a domain gets at least one full-length tile of a head (two under the
 // causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured break-even:
-// +7 % and more from there on, a loss below.)  The wide variant
-// rounds scale*log2(e)*Q to binary16, which costs accuracy in proportion to the size of the scores;
-// it is therefore only chosen for |scale| <= 2/sqrt(d), twice the usual softmax scale.
-SAW_HD bool wide_scale_ok(float scale, int d) { return scale * scale * (float)d <= 4.0f; }
-SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16, float scale) {
-    if (d != 128 || bf16 || !wide_scale_ok(scale, d)) return 32;
+// +7 % and more from there on, a loss below.)
+SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16) {
+    if (d != 128 || bf16) return 32;
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
     return (wide_tiles + parts - 1) / parts >= (causal ? 64 : 32) ? 64 : 32;

@@ -136,7 +136,7 @@ def main(argv=None):
             cache[key] = (Q, K, V, torch.empty_like(Q))
         Q, K, V, O = cache[key]
         var = sa.variant(**pt["variant"])
-        info = sa.attn_fwd_launch_info(*key, pt["causal"], var, "f16")
+        info = sa.attn_fwd_variant_launch_info(*key, pt["causal"], var, "f16")
         scale = 1.0 / math.sqrt(pt["d"])
 
         def launch():

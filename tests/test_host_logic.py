@@ -11,6 +11,7 @@ import torch
 
 from oracle import schedule_oracle as so
 from paper_2601_16032_amd import binding, traffic_model
+from tests.util import oracle_inputs
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -26,13 +27,22 @@ def test_library_exports_every_declared_symbol(sa):
     header = open(os.path.join(ROOT, "include", "sawattn.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", header)
-    assert set(names) >= {"attn_fwd", "attn_fwd_variant", "attn_fwd_launch_info", "attn_fwd_plan",
-                          "attn_fwd_workspace", "attn_fwd_workspace_bytes",
-                          "sawattn_mfma_probe", "sawattn_last_error", "sawattn_version"}
+    # the four entry points a caller of the method needs, under their plain names, and the rest
+    assert set(names) >= {"attn_fwd", "attn_fwd_launch_info", "attn_last_error", "attn_version"}
+    assert set(names) >= {"attn_fwd_variant", "attn_fwd_variant_launch_info", "attn_fwd_plan", "attn_fwd_workspace",
+                          "attn_fwd_workspace_bytes", "sawattn_last_error", "sawattn_version"}
     L = sa.lib()
     for n in names:
         assert hasattr(L, n), f"{n} is declared in sawattn.h but not exported"
-    assert sa.sawattn_version() >= 100
+    assert sa.attn_version() >= 200 and sa.sawattn_version() == sa.attn_version()
+    assert L.attn_last_error() is not None and sa.sawattn_last_error() == sa.attn_last_error()
+    # the benchmark's probe is a library of its own with a header of its own
+    probe = open(os.path.join(ROOT, "include", "sawattn_probe.h")).read()
+    probe = re.sub(r"/\*.*?\*/", "", probe, flags=re.S)
+    P = sa.probe_lib()
+    for n in re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", probe):
+        assert hasattr(P, n), f"{n} is declared in sawattn_probe.h but not exported"
+    assert not hasattr(L, "sawattn_mfma_probe")
 
 
 def test_argument_validation_without_a_gpu(sa):
@@ -50,24 +60,26 @@ def test_argument_validation_without_a_gpu(sa):
     assert call(Q=None) == binding.ERR_INVALID_ARG
     assert call(O=None) == binding.ERR_INVALID_ARG
     assert call(K=ok_ptr + 8) == binding.ERR_INVALID_ARG          # misaligned
-    assert "aligned" in sa.sawattn_last_error()
+    assert "aligned" in sa.attn_last_error()
     assert call(B=0) == binding.ERR_INVALID_ARG
     assert call(N=-5) == binding.ERR_INVALID_ARG
     assert call(d=96) == binding.ERR_UNSUPPORTED
-    assert "64 or 128" in sa.sawattn_last_error()
+    assert "64 or 128" in sa.attn_last_error()
     assert call(scale=float("nan")) == binding.ERR_INVALID_ARG
     assert call(scale=float("inf")) == binding.ERR_INVALID_ARG
     assert call(scan=2) == binding.ERR_INVALID_ARG
     assert call(idt=2) == binding.ERR_INVALID_ARG                 # fp32 inputs are not accepted
     assert call(odt=3) == binding.ERR_INVALID_ARG
     assert call(O=ok_ptr + 128 * 64 * 2 - 16) == binding.ERR_INVALID_ARG   # O starts inside Q
-    assert "overlap" in sa.sawattn_last_error()
+    assert "overlap" in sa.attn_last_error()
     assert call(Q=0x100000, K=0x200000, V=0x300000, O=0x300000 - 128 * 64 * 4 + 16, odt=2) == binding.ERR_INVALID_ARG
     assert call(B=1 << 20, H=1 << 10, N=1 << 20) == binding.ERR_INVALID_ARG   # size overflow
     with pytest.raises(binding.SawattnError):
         sa.attn_fwd_launch_info(1, 1, 128, 80)
-
-
+    info = binding.LaunchInfo()
+    assert L.attn_fwd_launch_info(1, 1, 128, 64, 0, 7, 0, ctypes.byref(info)) == binding.ERR_INVALID_ARG   # scan order
+    assert L.attn_fwd_launch_info(1, 1, 128, 64, 0, 1, 2, ctypes.byref(info)) == binding.ERR_INVALID_ARG   # fp32 inputs
+    assert L.attn_fwd_launch_info(1, 1, 128, 64, 0, 1, 0, None) == binding.ERR_INVALID_ARG
 # ------------------------------------------------------------------ schedule oracle: what must hold
 SHAPES = [(1, 1, 256), (1, 8, 2048), (1, 16, 8192), (1, 32, 16384), (4, 32, 32768), (2, 3, 333),
           (1, 12, 1000), (3, 7, 300), (1, 8, 128 * 70), (1, 2, 1), (5, 1, 129), (1, 64, 100)]
@@ -75,9 +87,10 @@ SHAPES = [(1, 1, 256), (1, 8, 2048), (1, 16, 8192), (1, 32, 16384), (4, 32, 3276
 
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N", SHAPES)
-def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
-    sched = so.schedule(B, H, N, causal, "sawtooth")
-    geo = so.launch_geometry(B, H, N, causal=causal)
+@pytest.mark.parametrize("tile_q,resident", [(128, 64), (256, 32), (128, 96), (64, 5)])
+def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal, tile_q, resident):
+    sched = so.schedule(B, H, N, causal, "sawtooth", tile_q=tile_q, resident=resident)
+    geo = so.launch_geometry(B, H, N, tile_q=tile_q, resident=resident)
     seen = {}
     for wg, recs in sched.items():
         for (head, t, first, last) in recs:
@@ -91,7 +104,7 @@ def test_schedule_oracle_covers_every_tile_once_and_alternates(B, H, N, causal):
     for (head, t), wg in seen.items():
         part = t % geo["parts"]
         assert wg % 8 == (head * geo["parts"] + part) % 8
-    cyc = so.schedule(B, H, N, causal, "cyclic")
+    cyc = so.schedule(B, H, N, causal, "cyclic", tile_q=tile_q, resident=resident)
     for wg in sched:
         assert [r[:2] for r in cyc[wg]] == [r[:2] for r in sched[wg]]   # same tiles, only direction differs
         assert all(r[2] == 0 for r in cyc[wg])
@@ -104,12 +117,20 @@ WIDE_VARIANTS = [dict(rows_per_wavefront=64), dict(rows_per_wavefront=64, launch
                  dict(rows_per_wavefront=64, decode="linear", slots_per_domain=3), dict(rows_per_wavefront=32)]
 
 
+def oracle_kw(kw, tile_q=128, resident=96):
+    """The schedule oracle's inputs for a variant description of the library (d = 64 kernel unless said otherwise)."""
+    out = {k: v for k, v in kw.items() if k in ("launch", "decode", "tiles_per_workgroup")}
+    out["tile_q"] = tile_q
+    out["resident"] = kw.get("slots_per_domain") or resident
+    return out
+
+
 @pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_schedule_oracle_variants_cover_every_tile_once(B, H, N, causal, kw):
-    sched = so.schedule(B, H, N, causal, "sawtooth", **kw)
-    geo = so.launch_geometry(B, H, N, causal=causal, **kw)
+    sched = so.schedule(B, H, N, causal, "sawtooth", **oracle_kw(kw))
+    geo = so.launch_geometry(B, H, N, **oracle_kw(kw))
     assert len(sched) == geo["grid"] and geo["grid"] % 8 == 0
     seen = set()
     for wg, recs in sched.items():
@@ -131,10 +152,10 @@ def test_schedule_oracle_variants_cover_every_tile_once(B, H, N, causal, kw):
 def test_schedule_oracle_linear_stride_by_hand():
     """Printed Alg. 2 on 3 heads x 5 tiles (N = 640) with G = 8: workgroup 1 takes linear indices
     1 and 9, i.e. (head 0, tile 1) forward and (head 1, tile 4) backward; workgroup 7 takes 7 only."""
-    s = so.schedule(1, 3, 640, False, "sawtooth", decode="linear", slots_per_domain=1)
+    s = so.schedule(1, 3, 640, False, "sawtooth", decode="linear", tile_q=128, resident=1)
     assert s[1] == [(0, 1, 0, 9), (1, 4, 9, 0)]
     assert s[7] == [(1, 2, 0, 9)]
-    g = so.schedule(1, 3, 640, True, "sawtooth", launch="grid", decode="linear")
+    g = so.schedule(1, 3, 640, True, "sawtooth", launch="grid", decode="linear", tile_q=128, resident=64)
     assert g[2] == [(0, 4, 0, 9), (1, 0, 1, 0)]              # indices 4, 5: last tile of head 0, first of head 1
 
 
@@ -154,34 +175,57 @@ def test_schedule_oracle_hand_example():
     """B*H = 8, N = 128*130: one head per domain, 64 slots, 3 rounds (64 + 64 + 2 tiles).
     Slot 5 of domain 3: round 0 -> tile 5 forward; round 1 (reverse hand-out) -> tile 64 + 58
     backward; round 2 (2 tiles, forward hand-out) -> nothing."""
-    s = so.schedule(1, 8, 128 * 130, False, "sawtooth", rows_per_wavefront=32)
+    s = so.schedule(1, 8, 128 * 130, False, "sawtooth", tile_q=128, resident=64)
     n_kv = 128 * 130 // 64
     assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 64 + 58, n_kv - 1, 0)]
     assert s[1 * 8 + 3] == [(3, 1, 0, n_kv - 1), (3, 64 + 62, n_kv - 1, 0), (3, 129, 0, n_kv - 1)]
 
 
 def test_schedule_oracle_hand_example_wide_tiles():
-    """Same with 64 rows per wavefront, which is the default at d = 128 for this length: N = 256*70 gives 70
-    tiles of 256 rows, 32 slots, 3 rounds (32 + 32 + 6).  Slot 5 of domain 3: tile 5 forward, tile 32 + 26
-    backward, tile 64 + 5 forward; slot 7 has no third tile."""
-    assert so.launch_geometry(1, 8, 256 * 70)["tile_q"] == 256 and so.launch_geometry(1, 8, 256 * 70)["slots"] == 32
-    s = so.schedule(1, 8, 256 * 70, False, "sawtooth")
+    """Same with 256-row tiles and 32 resident workgroups per domain: N = 256*70 gives 70 tiles, 3 rounds
+    (32 + 32 + 6).  Slot 5 of domain 3: tile 5 forward, tile 32 + 26 backward, tile 64 + 5 forward; slot 7 has no
+    third tile."""
+    s = so.schedule(1, 8, 256 * 70, False, "sawtooth", tile_q=256, resident=32)
     n_kv = 256 * 70 // 64
     assert s[5 * 8 + 3] == [(3, 5, 0, n_kv - 1), (3, 58, n_kv - 1, 0), (3, 69, 0, n_kv - 1)]
     assert s[7 * 8 + 3] == [(3, 7, 0, n_kv - 1), (3, 56, n_kv - 1, 0)]
-    # shorter sequences (fewer than 32 tiles per domain share of a head, 64 under the causal mask), head
-    # dimension 64, bfloat16 inputs, a scale beyond 2/sqrt(d), or a request for more than 32 workgroups per
-    # domain keep 128-row tiles
-    assert so.launch_geometry(1, 8, 256 * 31)["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 32)["tile_q"] == 256
-    assert so.launch_geometry(1, 8, 256 * 70, d=64)["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 70, dtype="bf16")["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 70, scale=0.5)["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 63, causal=True)["tile_q"] == 128
-    assert so.launch_geometry(1, 8, 256 * 64, causal=True)["tile_q"] == 256
-    assert so.launch_geometry(1, 8, 256 * 70, slots_per_domain=64)["tile_q"] == 128
-    assert so.launch_geometry(1, 1, 256 * 8 * 32)["tile_q"] == 256      # one head over all 8 domains: 32 tiles each
-    assert so.launch_geometry(1, 1, 256 * 8 * 31)["tile_q"] == 128
+
+
+# ------------------------------------------------------------------ the library's choice of kernel shape, case by case
+# (B, H, N, d, causal, dtype) -> (query rows per workgroup tile, workgroups per XCD, workgroups launched).
+# Resident workgroups per XCD: 32 CUs x 2 at d = 128 (64 KiB LDS, 256 registers each), x 3 at d = 64, x 1 with
+# 256-row tiles (128 KiB LDS, 512 registers).  256-row tiles where the measured break-even says so: d = 128,
+# binary16 inputs, at least 32 such tiles of a head per XCD (64 under the causal mask).
+KERNEL_CHOICE = [
+    ((1, 1, 256, 64, False, "f16"), (128, 1, 8)),           # workload 1: two tiles, one head over 8 XCDs
+    ((1, 8, 2048, 64, False, "f16"), (128, 16, 128)),       # workload 2: 16 tiles per head, one head per XCD
+    ((1, 16, 8192, 128, True, "bf16"), (128, 64, 512)),     # workload 3
+    ((1, 32, 16384, 128, False, "f16"), (256, 32, 256)),    # workload 4: 64 tiles of 256 rows per head
+    ((4, 32, 32768, 128, True, "bf16"), (128, 64, 512)),    # workload 5
+    ((1, 8, 256 * 31, 128, False, "f16"), (128, 62, 496)),  # one tile short of the break-even
+    ((1, 8, 256 * 32, 128, False, "f16"), (256, 32, 256)),
+    ((1, 8, 256 * 63, 128, True, "f16"), (128, 64, 512)),   # under the mask the break-even is twice as far out
+    ((1, 8, 256 * 64, 128, True, "f16"), (256, 32, 256)),
+    ((1, 8, 256 * 70, 64, False, "f16"), (128, 96, 768)),   # d = 64: three workgroups per CU
+    ((1, 8, 256 * 70, 128, False, "bf16"), (128, 64, 512)),
+    ((1, 1, 256 * 8 * 32, 128, False, "f16"), (256, 32, 256)),   # one head over 8 XCDs: 32 tiles each
+    ((1, 1, 256 * 8 * 31, 128, False, "f16"), (128, 62, 496)),
+    ((2, 3, 333, 128, False, "f16"), (128, 1, 8)),          # 6 heads: 4 parts per head, 3 tiles -> one per part
+]
+
+
+@pytest.mark.parametrize("shape,want", KERNEL_CHOICE)
+def test_kernel_choice_by_hand_listed_cases(sa, shape, want):
+    B, H, N, d, causal, dtype = shape
+    info = sa.attn_fwd_launch_info(B, H, N, d, causal, dtype=dtype)
+    assert (info["tile_q"], info["slots"], info["grid"]) == want
+    assert info == sa.attn_fwd_launch_info(B, H, N, d, causal, "cyclic", dtype)     # the order plays no part
+    assert info == sa.attn_fwd_variant_launch_info(B, H, N, d, causal, None, dtype)
+    assert info["tile_kv"] == 64 and info["block_threads"] == 256 and info["domains"] == 8
+    assert info["lds_bytes"] == {(128, 128): 65536, (128, 64): 32768, (256, 128): 131072}[(info["tile_q"], d)]
+    # a request for more workgroups per XCD than fit with 256-row tiles keeps 128-row tiles
+    if want[0] == 256:
+        assert sa.attn_fwd_variant_launch_info(B, H, N, d, causal, sa.variant(slots_per_domain=64), dtype)["tile_q"] == 128
 
 
 # ------------------------------------------------------------------ host plan == oracle
@@ -192,12 +236,12 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
     # d = 64 runs up to 96 workgroups per domain, d = 128 up to 64, or 32 of twice the size for long fp16 inputs
     for d, dtype in ((128, "f16"), (128, "bf16"), (64, "f16")):
         info = sa.attn_fwd_launch_info(B, H, N, d, causal, dtype=dtype)
-        geo = so.launch_geometry(B, H, N, d=d, causal=causal, dtype=dtype)
+        okw = oracle_inputs(info, d)
+        geo = so.launch_geometry(B, H, N, **okw)
         assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
         assert info["parts_per_head"] == geo["parts"] and info["q_tiles_per_head"] == geo["q_tiles"]
-        assert info["tile_q"] == geo["tile_q"]
         trace, count = sa.attn_fwd_plan(B, H, N, d, causal, order, dtype=dtype)
-        want = so.schedule(B, H, N, causal, order, d=d, dtype=dtype)
+        want = so.schedule(B, H, N, causal, order, **okw)
         for wg in range(info["grid"]):
             got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
             assert got == want[wg], f"workgroup {wg} d={d} {dtype}"
@@ -208,13 +252,13 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
     var = sa.variant(**kw)
-    info = sa.attn_fwd_launch_info(B, H, N, 64, causal, var)
-    geo = so.launch_geometry(B, H, N, d=64, causal=causal, **kw)
+    info = sa.attn_fwd_variant_launch_info(B, H, N, 64, causal, var)
+    geo = so.launch_geometry(B, H, N, **oracle_kw(kw))
     assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
     assert info["max_local_tiles"] == geo["max_local"]
     for order in ("cyclic", "sawtooth"):
         trace, count = sa.attn_fwd_plan(B, H, N, 64, causal, order, var)
-        want = so.schedule(B, H, N, causal, order, d=64, **kw)
+        want = so.schedule(B, H, N, causal, order, **oracle_kw(kw))
         for wg in range(info["grid"]):
             got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
             assert got == want[wg], f"workgroup {wg} {order}"
@@ -225,12 +269,14 @@ def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, causal, kw):
     var = sa.variant(**kw)
-    info = sa.attn_fwd_launch_info(B, H, N, 128, causal, var)
-    geo = so.launch_geometry(B, H, N, d=128, causal=causal, **kw)
-    assert info["tile_q"] == geo["tile_q"] == 4 * kw["rows_per_wavefront"]
+    info = sa.attn_fwd_variant_launch_info(B, H, N, 128, causal, var)
+    rows = kw["rows_per_wavefront"]
+    okw = oracle_kw(kw, tile_q=4 * rows, resident=32 if rows == 64 else 64)
+    geo = so.launch_geometry(B, H, N, **okw)
+    assert info["tile_q"] == 4 * rows
     assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"] and info["q_tiles_per_head"] == geo["q_tiles"]
     trace, count = sa.attn_fwd_plan(B, H, N, 128, causal, "sawtooth", var)
-    want = so.schedule(B, H, N, causal, "sawtooth", d=128, **kw)
+    want = so.schedule(B, H, N, causal, "sawtooth", **okw)
     seen = set()
     for wg in range(info["grid"]):
         got = [tuple(r) for r in trace[wg, : int(count[wg])].tolist()]
@@ -240,65 +286,44 @@ def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, 
 
 
 def test_variant_fields_are_validated(sa):
+    vli = sa.attn_fwd_variant_launch_info
     for bad in (dict(launch=2), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
                 dict(tiles_per_workgroup=3)):
         with pytest.raises(binding.SawattnError) as e:
-            sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(**bad))
+            vli(1, 8, 2048, 128, False, sa.variant(**bad))
         assert e.value.code == binding.ERR_INVALID_ARG and "variant." in str(e.value)
     with pytest.raises(binding.SawattnError) as e:
-        sa.attn_fwd_launch_info(1, 8, 2048, 64, False, sa.variant(rows_per_wavefront=64))
+        vli(1, 8, 2048, 64, False, sa.variant(rows_per_wavefront=64))
     assert e.value.code == binding.ERR_UNSUPPORTED
     with pytest.raises(binding.SawattnError) as e:     # 64 rows per wavefront: binary16 inputs only
-        sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64), dtype="bf16")
+        vli(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64), dtype="bf16")
     assert e.value.code == binding.ERR_UNSUPPORTED
     with pytest.raises(binding.SawattnError):
-        sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64, slots_per_domain=33))
+        vli(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64, slots_per_domain=33))
     with pytest.raises(binding.SawattnError):
-        sa.attn_fwd_launch_info(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=48))
-    assert sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=96))["slots"] == 96
+        vli(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=48))
+    assert vli(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=96))["slots"] == 96
     with pytest.raises(binding.SawattnError):
-        sa.attn_fwd_launch_info(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=97))
-
-
-@pytest.mark.parametrize("causal", [False, True])
-def test_default_rows_per_wavefront_depends_on_dtype_length_and_scale(sa, causal):
-    """64 rows per wavefront is the default only where it is both faster and as accurate: d = 128, binary16
-    inputs, long sequences, |scale| <= 2/sqrt(d) (it rounds scale*log2(e)*Q to binary16)."""
-    H, d = 8, 128
-    N = 256 * (64 if causal else 32)
-    usual = 1.0 / math.sqrt(d)
-    for dtype, n, scale, rows in (("f16", N, None, 64), ("f16", N, usual, 64), ("f16", N, -2.0 * usual, 64),
-                                  ("f16", N, 2.01 * usual, 32), ("f16", N, 1.0, 32), ("bf16", N, None, 32),
-                                  ("f16", N - 256, None, 32)):
-        info = sa.attn_fwd_launch_info(1, H, n, d, causal, dtype=dtype, scale=scale)
-        geo = so.launch_geometry(1, H, n, d=d, causal=causal, dtype=dtype, scale=scale)
-        assert info["tile_q"] == geo["tile_q"] == 4 * rows, (dtype, n, scale)
-        assert info["grid"] == geo["grid"]
-    assert sa.attn_fwd_launch_info(1, H, N, 64, causal)["tile_q"] == 128
-    with pytest.raises(binding.SawattnError) as e:
-        sa.attn_fwd_launch_info(1, H, N, d, causal, scale=float("inf"))
-    assert e.value.code == binding.ERR_INVALID_ARG
+        vli(1, 8, 128 * 200, 64, False, sa.variant(slots_per_domain=97))
 
 
 def test_workspace_bytes_follow_the_choice_of_kernel(sa):
     """A workspace is asked for exactly where bfloat16 inputs, once converted, would run the 64-row kernel."""
-    usual = None
-    for (B, H, N, d, causal, dtype, kw, scale, want_rows) in (
-            (4, 32, 32768, 128, True, "bf16", {}, usual, 64),            # workload 5
-            (1, 16, 8192, 128, True, "bf16", {}, usual, 32),             # workload 3: too short under the mask
-            (1, 16, 8192, 128, False, "bf16", {}, usual, 64),
-            (1, 16, 8192, 128, True, "bf16", dict(rows_per_wavefront=64), usual, 64),
-            (1, 16, 32768, 128, False, "bf16", dict(rows_per_wavefront=32), usual, 32),
-            (1, 16, 32768, 128, False, "bf16", {}, 1.0, 32),              # scale beyond 2/sqrt(d)
-            (1, 8, 32768, 64, False, "bf16", {}, usual, 32),
-            (1, 32, 16384, 128, False, "f16", {}, usual, 64)):            # binary16 needs no copies
+    for (B, H, N, d, causal, dtype, kw, want_rows) in (
+            (4, 32, 32768, 128, True, "bf16", {}, 64),            # workload 5
+            (1, 16, 8192, 128, True, "bf16", {}, 32),             # workload 3: too short under the mask
+            (1, 16, 8192, 128, False, "bf16", {}, 64),
+            (1, 16, 8192, 128, True, "bf16", dict(rows_per_wavefront=64), 64),
+            (1, 16, 32768, 128, False, "bf16", dict(rows_per_wavefront=32), 32),
+            (1, 8, 32768, 64, False, "bf16", {}, 32),
+            (1, 32, 16384, 128, False, "f16", {}, 64)):            # binary16 needs no copies
         var = sa.variant(**kw) if kw else None
-        need, info = sa.attn_fwd_workspace_bytes(B, H, N, d, causal, var, dtype, scale)
-        assert info["tile_q"] == 4 * want_rows, (B, H, N, d, causal, dtype, kw, scale)
+        need, info = sa.attn_fwd_workspace_bytes(B, H, N, d, causal, var, dtype)
+        assert info["tile_q"] == 4 * want_rows, (B, H, N, d, causal, dtype, kw)
         assert need == (4 * B * H * N * d if dtype == "bf16" and want_rows == 64 else 0)
         # the geometry is the binary16 one where copies are made, the plain one elsewhere
         as_if = "f16" if need else dtype
-        assert info == sa.attn_fwd_launch_info(B, H, N, d, causal, var, as_if, scale)
+        assert info == sa.attn_fwd_variant_launch_info(B, H, N, d, causal, var, as_if)
     with pytest.raises(binding.SawattnError):
         sa.attn_fwd_workspace_bytes(1, 8, 2048, 80, False)
 

@@ -1,4 +1,4 @@
-"""Shared helpers for the GPU parity tests (comparison metrics only; no attention arithmetic)."""
+"""Shared helpers for the tests (comparison metrics and launch facts only; no attention arithmetic)."""
 import numpy as np
 
 MAX_ABS_TOL = 2e-3     # stated tolerance of the benchmark definition, fp16/bf16 inputs
@@ -22,3 +22,20 @@ def assert_close(got, want, what=""):
     assert max_abs <= MAX_ABS_TOL and rel_l2 <= REL_L2_TOL, (
         f"{what}: max-abs {max_abs:.3e} (tol {MAX_ABS_TOL}), rel-L2 {rel_l2:.3e} (tol {REL_L2_TOL})")
     return max_abs, rel_l2
+
+
+# Workgroups of one XCD that run at the same time, by (head dimension, query rows per workgroup tile): 32 CUs times
+# the workgroups a CU holds (three at d = 64: 32 KiB LDS and at most 168 registers each; two at d = 128; one with
+# 256-row tiles, which take 128 KiB LDS and 512 registers per wavefront).  Listed here by hand: the schedule oracle
+# takes it as an input and the library's own figure is compared with it.
+RESIDENT_PER_XCD = {(64, 128): 96, (128, 128): 64, (128, 256): 32}
+
+
+def oracle_inputs(info, d, variant_kw=None):
+    """Inputs of oracle.schedule_oracle for a launch of the library: the tile height the library reports (its choice
+    is pinned case by case in test_host_logic.py), the hand-listed resident count, and the variant's hand-out."""
+    kw = dict(variant_kw or {})
+    out = {k: v for k, v in kw.items() if k in ("launch", "decode", "tiles_per_workgroup")}
+    out["tile_q"] = info["tile_q"]
+    out["resident"] = kw.get("slots_per_domain") or RESIDENT_PER_XCD[(d, info["tile_q"])]
+    return out
