@@ -9,7 +9,7 @@
  *
  * The four entry points a caller of the method needs are attn_fwd, attn_fwd_launch_info, attn_last_error
  * and attn_version.  The others serve the studies of the paper's Sec. 3 and Sec. 4.3 (launch variants,
- * recorded schedules), bfloat16 inputs with caller-provided scratch memory, and older names.
+ * recorded schedules), bfloat16 inputs with caller-provided or built-in scratch memory, and older names.
  */
 #ifndef SAWATTN_H
 #define SAWATTN_H
@@ -190,6 +190,28 @@ int attn_fwd_workspace(const void* Q, const void* K, const void* V, void* O,
  */
 int attn_fwd_workspace_bytes(int B, int H, int N, int d, int causal, int in_dtype,
                              const sawattn_variant* variant, size_t* bytes, sawattn_launch_info* info);
+
+/*
+ * attn_fwd_static -- attn_fwd for callers that may not allocate device memory and have no workspace to lend:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is attn_fwd_workspace
+ * with the default variant and no trace, the workspace being a fixed array of SAWATTN_STATIC_SCRATCH_BYTES in
+ * the library's device data (each GPU the library runs on holds its own copy from the time the library's code is
+ * loaded there until the process ends).  The call itself allocates and frees nothing, on the host or the device.
+ *
+ *   Arguments, stream behaviour and errors as attn_fwd.  In addition UNSUPPORTED, with the sizes in the error
+ *   text, if the problem would use more scratch than the array holds, i.e. if attn_fwd_workspace_bytes reports
+ *   more than SAWATTN_STATIC_SCRATCH_BYTES (bfloat16 inputs on the conversion path: 4*B*H*N*d bytes); problems
+ *   that use no scratch (binary16 inputs, short sequences, d = 64) have no size limit beyond attn_fwd's.
+ *   The first call on a device looks up the array's address there (hipGetSymbolAddress) and sets a kernel
+ *   attribute; make one call outside any stream capture first.
+ *   Every call on one GPU uses the same array, whose contents are overwritten by each call that needs it (nothing
+ *   in it has to start out zero): calls that overlap in time on one GPU -- two streams, two host threads -- race on
+ *   it and give wrong results; calls on one stream, or ordered by events, are safe.
+ */
+#define SAWATTN_STATIC_SCRATCH_BYTES (64u << 20)
+int attn_fwd_static(const void* Q, const void* K, const void* V, void* O,
+                    int B, int H, int N, int d, float scale, int causal, int scan_order,
+                    int in_dtype, int o_dtype, void* hip_stream);
 
 /*
  * attn_fwd_launch_info -- report the geometry attn_fwd would use (paper Sec. 2.2, Alg. 2: grid size and work

@@ -82,6 +82,8 @@ def lib() -> ctypes.CDLL:
         L.attn_fwd_workspace_bytes.restype = ci
         L.attn_fwd_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, pv, ctypes.POINTER(ctypes.c_size_t),
                                                ctypes.POINTER(LaunchInfo)]
+        L.attn_fwd_static.restype = ci
+        L.attn_fwd_static.argtypes = L.attn_fwd.argtypes
         L.attn_fwd_launch_info.restype = ci
         L.attn_fwd_launch_info.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(LaunchInfo)]
         L.attn_fwd_variant_launch_info.restype = ci
@@ -258,3 +260,16 @@ def attn_fwd_workspace(Q, K, V, O=None, *, scale: float, causal: bool = False, s
                                     workspace.numel() if workspace is not None else 0))
     return (O, tr, cnt) if trace else O
 
+
+
+def attn_fwd_static(Q, K, V, O=None, *, scale: float, causal: bool = False, scan_order="sawtooth", o_dtype=None,
+                    stream=None):
+    """attn_fwd with the library's fixed scratch array standing in for a workspace (the C call allocates nothing;
+    pass O to keep this wrapper from allocating the output)."""
+    O = _marshal(Q, K, V, O, o_dtype)
+    B, H, N, d = Q.shape
+    st = stream if stream is not None else torch.cuda.current_stream(Q.device)
+    _check(lib().attn_fwd_static(Q.data_ptr(), K.data_ptr(), V.data_ptr(), O.data_ptr(), B, H, N, d,
+                                 float(scale), int(bool(causal)), _SCAN_CODE[scan_order],
+                                 _DTYPE_CODE[Q.dtype], _DTYPE_CODE[O.dtype], st.cuda_stream))
+    return O

@@ -35,11 +35,16 @@
 #include <cstdio>
 #include <cstring>
 #include <initializer_list>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
 #include "sawattn.h"
 #include "schedule.h"
+
+// Scratch memory of attn_fwd_static (the entry point that may not allocate): binary16 copies of K and V.
+// In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[SAWATTN_STATIC_SCRATCH_BYTES];
 
 namespace sawattn {
 
@@ -1518,6 +1523,37 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     return ca ? launch<64, false, true, 1>(p, grid, stream) : launch<64, false, false, 1>(p, grid, stream);
 }
 
+// ---- scratch memory of attn_fwd_static: a fixed array in device memory instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy at its own address; host code never uses the array's name as
+// an address, only what hipGetSymbolAddress returned for the device that was current.
+constexpr size_t kStaticScratchBytes = (size_t)SAWATTN_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Address of `scratch` on the current device (looked up once per device).
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return fail(SAWATTN_ERR_RUNTIME, "cannot query the current device (or its index is 64 or more)");
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            char msg[200];
+            std::snprintf(msg, sizeof msg, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+            return fail(SAWATTN_ERR_RUNTIME, msg);
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SAWATTN_OK;
+}
+
 // Argument checks shared by the queries that launch nothing.
 int check_query(int B, int H, int N, int d, int in_dtype) {
     if (in_dtype != SAWATTN_F16 && in_dtype != SAWATTN_BF16)
@@ -1567,6 +1603,27 @@ int attn_fwd_workspace_bytes(int B, int H, int N, int d, int causal, int in_dtyp
     *bytes = use ? (size_t)B * H * N * d * 4 : 0;
     if (info) fill_info(s, d, info);
     return SAWATTN_OK;
+}
+
+int attn_fwd_static(const void* Q, const void* K, const void* V, void* O, int B, int H, int N, int d, float scale,
+                    int causal, int scan_order, int in_dtype, int o_dtype, void* hip_stream) {
+    using namespace sawattn;
+    size_t need = 0;
+    int rc = attn_fwd_workspace_bytes(B, H, N, d, causal, in_dtype, nullptr, &need, nullptr);
+    if (rc != SAWATTN_OK) return rc;
+    if (need > kStaticScratchBytes) {
+        char msg[200];
+        std::snprintf(msg, sizeof msg, "attn_fwd_static: this problem needs %zu bytes of scratch, the fixed array holds %zu "
+                      "(4*B*H*N*d must not exceed it)", need, kStaticScratchBytes);
+        return fail(SAWATTN_ERR_UNSUPPORTED, msg);
+    }
+    void* ws = nullptr;
+    if (need) {
+        rc = static_scratch(&ws);
+        if (rc != SAWATTN_OK) return rc;
+    }
+    return run(Q, K, V, O, B, H, N, d, scale, causal, scan_order, in_dtype, o_dtype, hip_stream, nullptr, nullptr, nullptr,
+               ws, need);
 }
 
 int attn_fwd_variant_launch_info(int B, int H, int N, int d, int causal, int in_dtype, const sawattn_variant* variant,

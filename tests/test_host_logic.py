@@ -80,6 +80,18 @@ def test_argument_validation_without_a_gpu(sa):
     assert L.attn_fwd_launch_info(1, 1, 128, 64, 0, 7, 0, ctypes.byref(info)) == binding.ERR_INVALID_ARG   # scan order
     assert L.attn_fwd_launch_info(1, 1, 128, 64, 0, 1, 2, ctypes.byref(info)) == binding.ERR_INVALID_ARG   # fp32 inputs
     assert L.attn_fwd_launch_info(1, 1, 128, 64, 0, 1, 0, None) == binding.ERR_INVALID_ARG
+    # the entry point with the built-in scratch array: the same checks, and its size limit, before anything runs
+    def static_call(**kw):
+        a = dict(base, **kw)
+        return L.attn_fwd_static(a["Q"], a["K"], a["V"], a["O"], a["B"], a["H"], a["N"], a["d"], a["scale"],
+                                 a["causal"], a["scan"], a["idt"], a["odt"], None)
+    assert static_call(Q=None) == binding.ERR_INVALID_ARG
+    assert static_call(d=96) == binding.ERR_UNSUPPORTED
+    big = dict(Q=1 << 40, K=2 << 40, V=3 << 40, O=4 << 40, B=1, H=8, N=32768, d=128, idt=1, odt=2)   # bf16, 128 MiB of copies
+    assert static_call(**big) == binding.ERR_UNSUPPORTED
+    assert "scratch" in sa.attn_last_error() and str(64 << 20) in sa.attn_last_error()
+
+
 # ------------------------------------------------------------------ schedule oracle: what must hold
 SHAPES = [(1, 1, 256), (1, 8, 2048), (1, 16, 8192), (1, 32, 16384), (4, 32, 32768), (2, 3, 333),
           (1, 12, 1000), (3, 7, 300), (1, 8, 128 * 70), (1, 2, 1), (5, 1, 129), (1, 64, 100)]
