@@ -112,13 +112,12 @@ typedef struct sawattn_variant {
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
                                 0 = default (2).  Ignored by the persistent launch. */
     int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
-                                64 (d = 128 and binary16 inputs only; UNSUPPORTED otherwise): 256 rows, one
-                                workgroup per CU (at most 32 per XCD), every K/V fragment read from LDS feeds
-                                two MFMAs; same arithmetic as the 32-row kernel;
-                                0 = default: 64 for d = 128, binary16 inputs, slots_per_domain <= 32 and
-                                sequences long enough that every workgroup of an XCD gets at least one 256-row
-                                tile of a head (two under the causal mask):
-                                ceil(ceil(N/256) / parts_per_head) >= 32 (64); else 32. */
+                                64 (d = 128 only; UNSUPPORTED otherwise): 256 rows, one workgroup per CU (at
+                                most 32 per XCD), every K/V fragment read from LDS feeds two MFMAs; same
+                                arithmetic as the 32-row kernel;
+                                0 = default: 64 for d = 128, slots_per_domain <= 32 and sequences long enough
+                                that every workgroup of an XCD gets at least one 256-row tile of a head (two
+                                under the causal mask): ceil(ceil(N/256) / parts_per_head) >= 32 (64); else 32. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round
@@ -160,9 +159,10 @@ typedef struct sawattn_launch_info {
 
 /*
  * attn_fwd_workspace -- attn_fwd_variant with scratch memory from the caller (paper Sec. 2.2, Alg. 1: the same
- * kernel; the scratch only changes the element type K and V are streamed in).  bfloat16 inputs normally run the
- * 32-rows-per-wavefront kernel, because the faster 64-row kernel needs binary16 operands.  Given a workspace, and
- * where that kernel would be chosen for the same problem in binary16 (d = 128, sequence long enough; or
+ * kernel; the scratch only changes the element type K and V are streamed in).  On bfloat16 inputs the kernels
+ * convert V to binary16 on its way into LDS, in every workgroup that streams it; the 64-rows-per-wavefront kernel,
+ * whose one wavefront per SIMD has no instruction slots to spare, pays for that (about 5 % on long sequences).
+ * Given a workspace, and where that kernel is chosen (d = 128, sequence long enough; or
  * variant.rows_per_wavefront = 64), the call first writes binary16 copies of K and V into the workspace with one
  * extra kernel on the same stream and then runs the 64-row kernel on them, converting Q as it is loaded.  The
  * copies are exact for bfloat16 magnitudes in [2^-14, 65504] and rounded to binary16 subnormals below (absolute

@@ -78,7 +78,6 @@ struct Params {
     int q_bf16;            // wide variant on converted inputs: Q is still bfloat16 (K and V are binary16 copies)
     int max_local;
     float c;               // |scale| * log2(e): scores are handled in the log2 domain
-    float thr;             // wide variant: the rescale slack in units of the raw score, kRescaleSlack / c
     Schedule sched;
 };
 
@@ -263,9 +262,17 @@ __device__ __forceinline__ float pair_sum(float x) {
 
 // Adds the two binary16 values of `ph` to two float partial sums (one mixed-precision FMA each:
 // exact, and cheaper in the instruction stream than the two-element dot product).
-__device__ __forceinline__ void add_pair(float& sum_lo, float& sum_hi, h2 ph) {
-    asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel_hi:[1,0,0]" : "+v"(sum_lo) : "v"(ph));
-    asm("v_fma_mix_f32 %0, %1, 1.0, %0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(sum_hi) : "v"(ph));
+// `one` is binary16 1.0 held in a register the compiler cannot see through (opaque_one()): the widened products
+// then become v_fma_mix_f32.  Written in C and not as inline assembly because the compiler separates dependent
+// assembly statements that have nothing in between by a no-op each, one issue slot per row-sum update.
+__device__ __forceinline__ _Float16 opaque_one() {
+    _Float16 one = (_Float16)1.0f;
+    asm volatile("" : "+v"(one));
+    return one;
+}
+__device__ __forceinline__ void add_pair(float& sum_lo, float& sum_hi, h2 ph, _Float16 one) {
+    sum_lo = __builtin_fmaf((float)ph[0], (float)one, sum_lo);
+    sum_hi = __builtin_fmaf((float)ph[1], (float)one, sum_hi);
 }
 
 // The running maximum is only raised when a tile's maximum exceeds it by more than this many
@@ -313,12 +320,6 @@ __device__ __forceinline__ void mfma_s(f16v& acc, u4 k_frag, const u4& q_frag) {
     if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
     else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(k_frag), "a"(q_frag));
 }
-// First MFMA of an S^T block whose accumulator starts from the register block `init`.
-template <bool BF16>
-__device__ __forceinline__ void mfma_s_init(f16v& acc, u4 k_frag, const u4& q_frag, const f16v& init) {
-    if constexpr (BF16) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(acc) : "v"(k_frag), "a"(q_frag), "v"(init));
-    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3" : "=&v"(acc) : "v"(k_frag), "a"(q_frag), "v"(init));
-}
 __device__ __forceinline__ void mfma_o(f16v& acc, s8 v_frag, const u4& p_frag) {
     asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(v_frag), "v"(p_frag));
 }
@@ -350,8 +351,8 @@ __device__ __forceinline__ void mfma_guard(f16v (&acc)[NACC]) {
 // WIDE: the tile state is the wide variant's -- Q^T fragments and O^T accumulators live in accumulation
 // registers and the MFMAs are the written-out ones.
 template <int D, bool BF16, bool CAUSAL, bool MASKED, bool WIDE = false>
-__device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>& ra, float c, float thr, int kv0, int qrow,
-                                             int lane, int N) {
+__device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>& ra, float c, int kv0, int qrow, int lane,
+                                             int N) {
     using G = Geo<D>;
     constexpr int KS = D / 16, DB = D / 32;
     const int g = lane >> 5;
@@ -407,12 +408,10 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 #pragma unroll
     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[1][r]);
     mx = pair_max(mx);
-    // The wide variant keeps its reference maximum in units of the raw score (its pipelined loop lets the
-    // MFMAs start from -M); the other kernels keep it in the log2 domain.
-    const float tmax = WIDE ? mx : mx * c;
-    if (__builtin_amdgcn_ballot_w64(tmax > st.M + (WIDE ? thr : kRescaleSlack)) != 0) {
+    const float tmax = mx * c;
+    if (__builtin_amdgcn_ballot_w64(tmax > st.M + kRescaleSlack) != 0) {
         const float Mnew = fmaxf(st.M, tmax);
-        const float alpha = (st.M == -INFINITY) ? 1.0f : fast_exp2(WIDE ? c * (st.M - Mnew) : st.M - Mnew);
+        const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st.M - Mnew);
         st.M = Mnew;
         st.L *= alpha;
 #pragma unroll
@@ -432,8 +431,8 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int r = 8 * h + 2 * i;
-                float x0 = fast_exp2(WIDE ? c * (s[b][r] - Mref) : __builtin_fmaf(s[b][r], c, -Mref));
-                float x1 = fast_exp2(WIDE ? c * (s[b][r + 1] - Mref) : __builtin_fmaf(s[b][r + 1], c, -Mref));
+                float x0 = fast_exp2(__builtin_fmaf(s[b][r], c, -Mref));
+                float x1 = fast_exp2(__builtin_fmaf(s[b][r + 1], c, -Mref));
                 if constexpr (MASKED) {
                     if ((masked >> (16 * b + r)) & 1u) x0 = 0.f;
                     if ((masked >> (16 * b + r + 1)) & 1u) x1 = 0.f;
@@ -479,7 +478,7 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 // and, while computing, fetches the tile of iteration it+1 into the other pair.
 template <int D, bool BF16, bool CAUSAL, bool MASKED, int NH>
 __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const LaneMap<D>& lm, const char* Kh, const char* Vh, int N,
-                                              float c, float thr, int j_first, int step, int count, int qw0, int qrow, int lane,
+                                              float c, int j_first, int step, int count, int qw0, int qrow, int lane,
                                               LDS_PTR(char) lds) {
     using G = Geo<D>;
     if (count <= 0) return;
@@ -520,7 +519,7 @@ __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const Lane
 #pragma unroll
         for (int h = 0; h < NH; ++h) {   // half h: query rows qw0 + 32h .. +31 (this lane: qrow + 32h)
             const bool active = qw0 + 32 * h < N && (!CAUSAL || kv0 <= qw0 + 32 * h + 31);
-            if (active) compute_tile<D, BF16, CAUSAL, MASKED, NH == 2>(st[h], ra, c, thr, kv0, qrow + 32 * h, lane, N);
+            if (active) compute_tile<D, BF16, CAUSAL, MASKED, NH == 2>(st[h], ra, c, kv0, qrow + 32 * h, lane, N);
         }
         ra.flip(cur ? -G::kTile : G::kTile);
         if (more) {
@@ -552,6 +551,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
     float L_hi = 0.f;   // second partial of the running sum (upper halves of the probability pairs), folded into st.L
+    const _Float16 one = opaque_one();
     const f16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     f16v A[2];          // S^T of the tile one ahead: block b = keys 32b..32b+31 of the tile
     float x[32];        // score*c - M of the current tile, index 16*b + r
@@ -601,7 +601,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
         if (u >= 1 && u <= 16) {
             const int v = u - 1;
             const h2 ph = __builtin_convertvector(f2{e0[v], e1[v]}, h2);
-            add_pair(st.L, L_hi, ph);   // sum of the rounded probabilities, the values the second product uses
+            add_pair(st.L, L_hi, ph, one);   // sum of the rounded probabilities, the values the second product uses
             pf[v / 4][v % 4] = __builtin_bit_cast(unsigned, ph);
         }
     };
@@ -819,7 +819,7 @@ constexpr int kWideLdsBytes = 2 * kWideBuffers * Geo<128>::kTile;
 
 template <bool BF16>
 __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], const LaneMap<128>& lm, const char* Kh,
-                                                     const char* Vh, float c, float thr, int j_first, int step, int count,
+                                                     const char* Vh, float c, int j_first, int step, int count, int lane,
                                                      LDS_PTR(char) lds) {
     constexpr int D = 128;
     using G = Geo<D>;
@@ -832,11 +832,17 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
     float L_hi[2] = {0.f, 0.f};   // second partials of the running sums, folded into st[h].L
-    f16v S[2][2];                 // [half][block]: score - M; pair u = 0..15 of a half is S[h][u / 8][2 * (u % 8) .. + 1]
-    f16v negM[2];                 // [half]: -M in all 16 registers, the initial accumulator of an S^T block
+    const _Float16 one = opaque_one();
+    f16v S[2][2];                 // [half][block]: raw scores; pair u = 0..15 of a half is S[h][u / 8][2 * (u % 8) .. + 1]
+    float nM[2], lim[2];          // [half]: -M (log2 domain), and the raw score above which M has to be raised
     u4 pf[2][4];                  // [half][contraction step]: probabilities as B operands; pair u is pf[h][u / 4][u % 4]
     float e0[2][16], e1[2][16];
-    float tmax_ahead[2] = {0.f, 0.f};   // this lane's maximum of the tile one ahead, relative to M
+    float tmax_ahead[2] = {0.f, 0.f};   // this lane's maximum of the raw scores of the tile one ahead (never below lim)
+    // bfloat16 inputs: K stays bfloat16 (direct loads, bfloat16 MFMAs for S^T); V travels global -> registers ->
+    // binary16 -> LDS, because the probabilities are binary16.  vreg holds this wavefront's share of the V tile one
+    // ahead between its load (end of an iteration) and its conversion (under the second-block MFMAs of the next).
+    u4 vreg[NL];
+    const unsigned v_store = lds0 + VB + lm.fill_dst + lane * 16;   // this lane's 16 bytes of load 0 in V buffer 0
     mfma_guard(st[0].o);
     mfma_guard(st[1].o);
 
@@ -865,7 +871,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     // Softmax work items of half h, pair u = 0..15: the two exponentials, the convert into the B operand,
     // the addition to the running sum.
     auto exp2_pair = [&](int h, int u) {
-        const float x0 = c * S[h][u / 8][2 * (u % 8)], x1 = c * S[h][u / 8][2 * (u % 8) + 1];
+        const float x0 = __builtin_fmaf(S[h][u / 8][2 * (u % 8)], c, nM[h]);
+        const float x1 = __builtin_fmaf(S[h][u / 8][2 * (u % 8) + 1], c, nM[h]);
         e0[h][u] = fast_exp2(x0);
         e1[h][u] = fast_exp2(x1);
     };
@@ -874,15 +881,15 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     };
     auto sum_pair = [&](int h, int u) {
         const unsigned word = pf[h][u / 4][u % 4];   // (a copy: bit casts of a vector element do not read that element)
-        add_pair(st[h].L, L_hi[h], __builtin_bit_cast(h2, word));
+        add_pair(st[h].L, L_hi[h], __builtin_bit_cast(h2, word), one);
     };
     auto first_block_probabilities = [&](int h) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) { exp2_pair(h, u); convert_pair(h, u); }
     };
-    auto set_negM = [&](int h) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) negM[h][r] = -st[h].M;
+    auto set_reference = [&](int h) {
+        nM[h] = -st[h].M;
+        lim[h] = c > 0.f ? (st[h].M + kRescaleSlack) / c : INFINITY;
     };
 
     // ---------------------------------------------------------------- prologue: K(0..2), V(0..1) on their way, S(0)
@@ -890,10 +897,22 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     for (int i = 0; i < 3; ++i) {
 #pragma unroll
         for (int l = 0; l < NL; ++l) fetch_k(i, l);
-        if (i < 2) {
+        if constexpr (!BF16) {
+            if (i < 2) {
 #pragma unroll
-            for (int l = 0; l < NL; ++l) fetch_v(i, l);
+                for (int l = 0; l < NL; ++l) fetch_v(i, l);
+            }
         }
+    }
+    if constexpr (BF16) {
+        // V(0) goes through registers into buffer 0 now, V(1) waits in vreg for the first iteration
+        u4 v0[NL];
+#pragma unroll
+        for (int l = 0; l < NL; ++l) v0[l] = *reinterpret_cast<const u4*>(tile_base(Vh, 0) + lm.fill_src[l]);
+#pragma unroll
+        for (int l = 0; l < NL; ++l) vreg[l] = *reinterpret_cast<const u4*>(tile_base(Vh, 1) + lm.fill_src[l]);
+#pragma unroll
+        for (int l = 0; l < NL; ++l) *(LDS_PTR(u4))(size_t)(v_store + l * 4096) = bf16x8_to_f16x8(v0[l]);
     }
     wait_tile_landed();
     __syncthreads();
@@ -923,13 +942,13 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             float mx = fmaxf(S[h][0][0], S[h][0][1]);
 #pragma unroll
             for (int r = 2; r < 32; r += 2) mx = fmaxf(fmaxf(mx, S[h][r >> 4][r & 15]), S[h][r >> 4][(r & 15) + 1]);
-            const float tmax = pair_max(mx);
+            const float tmax = pair_max(mx) * c;
             // the first tile of a query tile finds M = -inf and takes its own maximum as the reference
-            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + thr)) != 0) {
+            if (__builtin_amdgcn_ballot_w64(!(tmax <= st[h].M + kRescaleSlack)) != 0) {
                 st[h].L += L_hi[h];
                 L_hi[h] = 0.f;
                 const float Mnew = fmaxf(st[h].M, tmax);
-                const float alpha = (st[h].M == -INFINITY) ? 1.0f : fast_exp2(c * (st[h].M - Mnew));
+                const float alpha = (Mnew == -INFINITY) ? 1.0f : fast_exp2(st[h].M - Mnew);
                 st[h].M = Mnew;
                 st[h].L *= alpha;
 #pragma unroll
@@ -937,9 +956,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 #pragma unroll
                     for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
             }
-#pragma unroll
-            for (int r = 0; r < 32; ++r) S[h][r >> 4][r & 15] -= st[h].M;
-            set_negM(h);
+            set_reference(h);
             first_block_probabilities(h);
         }
         mfma_guard(st[0].o);
@@ -979,7 +996,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const int t = 2 * q + h;
-                    if (q % 8 == 0) mfma_s_init<BF16>(S[h][b], a[n], st[h].qf[ks], negM[h]);   // the block's first MFMA
+                    if (q % 8 == 0) mfma_s_first<BF16>(S[h][b], a[n], st[h].qf[ks]);   // the block's first MFMA
                     else mfma_s<BF16>(S[h][b], a[n], st[h].qf[ks]);
                     if (t < 16) {
                         // exponentials of the second block of tile i: pair 8 + t/2 of half t%2, convert of the one before
@@ -995,6 +1012,17 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                         const int w0 = 2 * (t - 16);
                         sum_pair(w0 & 1, w0 >> 1);
                         sum_pair((w0 + 1) & 1, (w0 + 1) >> 1);
+                        if constexpr (BF16) {
+                            // one word of V(i+1) from bfloat16 to binary16; every fourth completes 16 bytes for LDS
+                            const int w = t - 16;
+                            const unsigned word = vreg[w / 4][w % 4];
+                            f2 y;
+                            y[0] = __builtin_bit_cast(float, word << 16);
+                            y[1] = __builtin_bit_cast(float, word & 0xffff0000u);
+                            vreg[w / 4][w % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(y, h2));
+                            if (w % 4 == 3)
+                                *(LDS_PTR(u4))(size_t)(v_store + ((i + 1) & 3) * G::kTile + (w / 4) * 4096) = vreg[w / 4];
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -1016,10 +1044,14 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             if (li == 1) load_to_lds_16B_at<4096>(kbase, lm.fill_src[1], kdst_s);
             if (li == 2) load_to_lds_16B_at<8192>(kbase, lm.fill_src[2], kdst_s);
             if (li == 3) load_to_lds_16B_at<12288>(kbase, lm.fill_src[3], kdst_s);
-            if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
-            if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
-            if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
-            if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
+            if constexpr (BF16) {
+                if (li >= 4) vreg[li - 4] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[li - 4]);
+            } else {
+                if (li == 4) load_to_lds_16B_at<0>(vbase, lm.fill_src[0], vdst_s);
+                if (li == 5) load_to_lds_16B_at<4096>(vbase, lm.fill_src[1], vdst_s);
+                if (li == 6) load_to_lds_16B_at<8192>(vbase, lm.fill_src[2], vdst_s);
+                if (li == 7) load_to_lds_16B_at<12288>(vbase, lm.fill_src[3], vdst_s);
+            }
         };
 #pragma unroll
         for (int idx = 0; idx < NB; ++idx) {
@@ -1046,14 +1078,14 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
                     for (int q = 0; q < 4; ++q) {
                         const int n = (t - 2) * 4 + q, hh = n & 1, op = n >> 1;    // op-th max3 of half hh
                         const float u0 = S[hh][(2 * op) >> 4][(2 * op) & 15], u1 = S[hh][(2 * op) >> 4][((2 * op) & 15) + 1];
-                        mx[hh] = op == 0 ? fmaxf(u0, u1) : fmaxf(fmaxf(mx[hh], u0), u1);
+                        mx[hh] = fmaxf(fmaxf(op == 0 ? lim[hh] : mx[hh], u0), u1);   // (starts from lim: exceeds it exactly when a score does)
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
                 if (t == 10) {
                     tmax_ahead[0] = mx[0];
                     tmax_ahead[1] = mx[1];
-                    need = __builtin_amdgcn_ballot_w64(!(mx[0] <= thr) || !(mx[1] <= thr)) != 0;
+                    need = __builtin_amdgcn_ballot_w64(!(mx[0] <= lim[0]) || !(mx[1] <= lim[1])) != 0;
                 }
                 if (t >= 10 && t < 18) {            // pairs 0..3 of both halves: pf[.][0]
                     const int hh = t & 1, u = (t - 10) / 2;
@@ -1094,25 +1126,23 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
             float t = tmax_ahead[h];
             asm volatile("" : "+v"(t));
             t = pair_max(t);     // the two lanes of a query row move together
-            if (__builtin_amdgcn_ballot_w64(!(t <= thr)) != 0) {
-                const float up = fmaxf(t, 0.f);
-                const float alpha = fast_exp2(-c * up);
-                st[h].M += up;
+            const bool mine = !(t <= lim[h]);   // (t is the row's maximum only where it exceeds lim)
+            if (__builtin_amdgcn_ballot_w64(mine) != 0) {
+                const float Mnew = mine ? fmaxf(st[h].M, t * c) : st[h].M;
+                const float alpha = fast_exp2(st[h].M - Mnew);
+                st[h].M = Mnew;
                 st[h].L = (st[h].L + L_hi[h]) * alpha;
                 L_hi[h] = 0.f;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) st[h].o[db][r] *= alpha;
-#pragma unroll
-                for (int r = 0; r < 32; ++r) S[h][r >> 4][r & 15] -= up;
-                set_negM(h);
+                set_reference(h);
                 first_block_probabilities(h);
             }
         }
         mfma_guard(st[0].o);
         mfma_guard(st[1].o);
-        asm volatile("s_nop 3" : "+v"(negM[0]), "+v"(negM[1]));   // written by vector instructions, read by the next MFMAs
     };
     int i = 0;
     while (i + 1 < count) {
@@ -1184,7 +1214,9 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
             v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
             if constexpr (NH == 2) {
-                if (p.q_bf16) v = bf16x8_to_f16x8(v);   // K and V are binary16 copies: Q follows (exact for normal binary16 magnitudes)
+                if constexpr (!BF16) {
+                    if (p.q_bf16) v = bf16x8_to_f16x8(v);   // K and V are binary16 copies: Q follows (exact for normal binary16 magnitudes)
+                }
                 asm volatile("" : "=a"(st[h].qf[ks]) : "0"(v));   // accumulation registers from here on
             } else {
                 st[h].qf[ks] = v;
@@ -1197,7 +1229,7 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         st[h].M = -INFINITY;
         st[h].L = 0.f;
     }
-    const float c = p.c, thr = p.thr;
+    const float c = p.c;
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
     // the tiles that reach past the first row of this query tile.  They sit at one end of the scan,
@@ -1215,17 +1247,17 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             int l2 = lane;
             asm volatile("" : "+v"(l2));
             const LaneMap<D> lm2(wave, l2);
-            pipelined_range_wide<BF16>(st, lm2, Kh, Vh, c, thr, j_first, step, n_plain, lds);
+            pipelined_range_wide<BF16>(st, lm2, Kh, Vh, c, j_first, step, n_plain, l2, lds);
         }
     };
     auto masked = [&](int j_first) {
         if constexpr (NH == 1) {
-            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, thr, j_first, step, n_masked, qw0, qrow, lane, lds);
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, lane, lds);
         } else {
             int l2 = lane;
             asm volatile("" : "+v"(l2));
             const LaneMap<D> lm2(wave, l2);
-            general_range<D, BF16, CAUSAL, true, NH>(st, lm2, Kh, Vh, N, c, thr, j_first, step, n_masked, qw0, qrow, l2, lds);
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm2, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, l2, lds);
         }
     };
     if (step > 0) {
@@ -1404,8 +1436,8 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.decode must be SAWATTN_DECODE_DOMAIN or SAWATTN_DECODE_LINEAR");
         if (v->rows_per_wavefront != 0 && v->rows_per_wavefront != 32 && v->rows_per_wavefront != 64)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.rows_per_wavefront must be 0 (default), 32 or 64");
-        if (v->rows_per_wavefront == 64 && (d != 128 || bf16))
-            return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128 and binary16 inputs");
+        if (v->rows_per_wavefront == 64 && d != 128)
+            return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
         rows = v->rows_per_wavefront;
         if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16);
         if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : kTileQ))
@@ -1494,7 +1526,6 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.negate_q = scale < 0.f;
     p.q_bf16 = converted;
     p.c = (float)(std::fabs((double)scale) * 1.4426950408889634074);
-    p.thr = p.c > 0.f ? std::min(kRescaleSlack / p.c, 1e30f) : 1e30f;
     p.sched = sched;
     p.max_local = sched.local_iters;
     const int grid = sched.grid;
@@ -1513,6 +1544,7 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         p.V = V16;
     }
     if (sched.tile_q > kTileQ) {
+        if (bf && !converted) return ca ? launch<128, true, true, 2>(p, grid, stream) : launch<128, true, false, 2>(p, grid, stream);
         return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
     if (d == 128) {

@@ -47,7 +47,8 @@ SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b);
 // causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured break-even:
 // +7 % and more from there on, a loss below.)
 SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16) {
-    if (d != 128 || bf16) return 32;
+    (void)bf16;
+    if (d != 128) return 32;
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
     return (wide_tiles + parts - 1) / parts >= (causal ? 64 : 32) ? 64 : 32;

@@ -306,13 +306,15 @@ def test_variants_at_full_size_agree_with_default(sa):
 
 # ------------------------------------------------------------------ 64 query rows per wavefront (d = 128)
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "bf16-workspace"])
 def test_wide_rows_variant_small_shapes(sa, oracle, dtype, causal):
     """256-row workgroup tiles, every length class: shorter than a tile, ragged, one and several tiles,
     both scan orders, also under the direct launch (second tile backward) and with few slots (many rounds).
-    bfloat16 inputs reach this kernel through binary16 copies in a workspace."""
+    bfloat16 inputs run this kernel as they are (V converted on its way into LDS) or, given a workspace, through
+    binary16 copies of K and V."""
     from oracle import schedule_oracle as so
-    call = sa.attn_fwd_workspace if dtype == "bf16" else sa.attn_fwd_variant
+    call = sa.attn_fwd_workspace if dtype == "bf16-workspace" else sa.attn_fwd_variant
+    dtype = dtype.split("-")[0]
     for k, N in enumerate([1, 63, 64, 65, 200, 256, 257, 511, 512, 777, 1000, 2048 + 33]):
         B, H = (1, 2) if k % 2 == 0 else (2, 3)
         Q, K, V = workloads.make_random(B, H, N, 128, dtype, seed=2000 + N)
@@ -331,16 +333,17 @@ def test_wide_rows_variant_small_shapes(sa, oracle, dtype, causal):
                     assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == recs, f"workgroup {wg}"
 
 
+@pytest.mark.parametrize("dtype", [torch.float16, torch.bfloat16])
 @pytest.mark.parametrize("scale_factor", [1.0, 8.0])
 @pytest.mark.parametrize("causal", [False, True])
-def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal, scale_factor):
+def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal, scale_factor, dtype):
     """A sequence long enough that the library picks 64 rows per wavefront by itself (two rounds of 32 slots per
     head), with score levels that jump from tile to tile by far more than the slack, so that the reference
     maximum is raised again and again in both scan directions.  Every row is compared with the oracle, at the
     usual scale (scores step by up to 53) and at eight times that (steps of several hundred)."""
     H, N, d = 8, (256 * 128 if causal else 256 * 64) + 100, 128
     scale = scale_factor / math.sqrt(d)
-    assert sa.attn_fwd_launch_info(1, H, N, d, causal)["tile_q"] == 256
+    assert sa.attn_fwd_launch_info(1, H, N, d, causal, dtype=dtype)["tile_q"] == 256
     g = torch.Generator("cpu").manual_seed(99)
     level = 60.0 * torch.rand(H, (N + 63) // 64, generator=g)
     level[:, 7] = 75.0
@@ -350,7 +353,7 @@ def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal, scale_f
     Q = 3.0 * torch.randn(1, H, N, d, generator=g)
     Q[0, :, :, 0] = 8.0          # scores step by up to 8 * 75 * scale = 53 between tiles
     V = torch.randn(1, H, N, d, generator=g)
-    Q, K, V = Q.half(), K.half(), V.half()
+    Q, K, V = Q.to(dtype), K.to(dtype), V.to(dtype)
     # every row of two heads, sampled rows of the others
     rows = list(range(0, N, 389)) + [N - 1]
     want_all = oracle.attention(Q[:, :2], K[:, :2], V[:, :2], scale, causal=causal)
@@ -370,14 +373,14 @@ def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal, scale_f
 
 @pytest.mark.parametrize("seed", [1, 2])
 def test_wide_kernel_random_shapes_and_score_patterns(sa, oracle, seed):
-    """Seeded random cases for the 64-rows-per-wavefront kernel (bf16 ones through the workspace): lengths around
+    """Seeded random cases for the 64-rows-per-wavefront kernel (bf16 ones directly and through the workspace): lengths around
     the tile boundaries, few slots (many rounds), both launches and orders, any scale, and three score patterns --
     plain N(0,1), levels that jump between 64-key tiles by up to 40 score units, and a ramp that raises the maximum
     on every tile in one scan direction and never in the other."""
     rng = np.random.default_rng(seed)
     d = 128
     for case in range(30):
-        dtype = str(rng.choice(["f16", "bf16"]))
+        dtype = str(rng.choice(["f16", "bf16", "bf16-workspace"]))
         causal = bool(rng.integers(0, 2))
         B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
         N = int(rng.choice([rng.integers(1, 70), rng.integers(60, 400), rng.integers(250, 1400), rng.integers(1000, 3000)]))
@@ -398,7 +401,7 @@ def test_wide_kernel_random_shapes_and_score_patterns(sa, oracle, seed):
         want = oracle.attention(Q, K, V, scale, causal=causal)
         var = sa.variant(rows_per_wavefront=64, slots_per_domain=int(rng.choice([0, 1, 2])),
                          launch=str(rng.choice(["persistent", "grid"])))
-        call = sa.attn_fwd_workspace if dtype == "bf16" else sa.attn_fwd_variant
+        call = sa.attn_fwd_workspace if dtype == "bf16-workspace" else sa.attn_fwd_variant
         O = call(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order, o_dtype=torch.float32,
                  variant=var)
         torch.cuda.synchronize()
@@ -411,7 +414,7 @@ def test_wide_kernel_random_shapes_and_score_patterns(sa, oracle, seed):
 def test_workspace_path_small_shapes(sa, oracle, causal):
     """bfloat16 inputs with a workspace and 64 rows per wavefront: K and V go through binary16 copies, Q is
     converted as it is loaded.  Every length class, both scan orders, schedule as for binary16 inputs; the caller's
-    tensors stay untouched; without a workspace the same request is refused."""
+    tensors stay untouched; without a workspace the same request runs the kernel on the bfloat16 tensors."""
     from oracle import schedule_oracle as so
     var = sa.variant(rows_per_wavefront=64)
     for k, N in enumerate([1, 63, 64, 65, 200, 256, 257, 511, 777, 2048 + 33]):
@@ -440,9 +443,9 @@ def test_workspace_path_small_shapes(sa, oracle, causal):
         assert torch.equal(half[half.numel() // 2:].view(B, H, N, 128).cpu(), V.float().half())
         big = K.float().abs() >= 2.0 ** -14
         assert torch.equal(K.float().half().float()[big], K.float()[big])
-    with pytest.raises(binding.SawattnError) as e:
-        sa.attn_fwd_variant(Qd, Kd, Vd, scale=scale, causal=causal, variant=var)
-    assert e.value.code == binding.ERR_UNSUPPORTED
+    direct = sa.attn_fwd_variant(Qd, Kd, Vd, scale=scale, causal=causal, o_dtype=torch.float32, variant=var)
+    torch.cuda.synchronize()
+    assert_close(direct.double().cpu().numpy(), want, f"same request without a workspace causal={causal}")
     with pytest.raises(binding.SawattnError) as e:     # too small a workspace
         sa.attn_fwd_workspace(Qd, Kd, Vd, scale=scale, causal=causal, variant=var, workspace=ws[: need - 16])
     assert e.value.code == binding.ERR_INVALID_ARG

@@ -207,19 +207,19 @@ def test_schedule_oracle_hand_example_wide_tiles():
 # (B, H, N, d, causal, dtype) -> (query rows per workgroup tile, workgroups per XCD, workgroups launched).
 # Resident workgroups per XCD: 32 CUs x 2 at d = 128 (64 KiB LDS, 256 registers each), x 3 at d = 64, x 1 with
 # 256-row tiles (128 KiB LDS, 512 registers).  256-row tiles where the measured break-even says so: d = 128,
-# binary16 inputs, at least 32 such tiles of a head per XCD (64 under the causal mask).
+# at least 32 such tiles of a head per XCD (64 under the causal mask).
 KERNEL_CHOICE = [
     ((1, 1, 256, 64, False, "f16"), (128, 1, 8)),           # workload 1: two tiles, one head over 8 XCDs
     ((1, 8, 2048, 64, False, "f16"), (128, 16, 128)),       # workload 2: 16 tiles per head, one head per XCD
     ((1, 16, 8192, 128, True, "bf16"), (128, 64, 512)),     # workload 3
     ((1, 32, 16384, 128, False, "f16"), (256, 32, 256)),    # workload 4: 64 tiles of 256 rows per head
-    ((4, 32, 32768, 128, True, "bf16"), (128, 64, 512)),    # workload 5
+    ((4, 32, 32768, 128, True, "bf16"), (256, 32, 256)),    # workload 5: 128 tiles of 256 rows per head
     ((1, 8, 256 * 31, 128, False, "f16"), (128, 62, 496)),  # one tile short of the break-even
     ((1, 8, 256 * 32, 128, False, "f16"), (256, 32, 256)),
     ((1, 8, 256 * 63, 128, True, "f16"), (128, 64, 512)),   # under the mask the break-even is twice as far out
     ((1, 8, 256 * 64, 128, True, "f16"), (256, 32, 256)),
     ((1, 8, 256 * 70, 64, False, "f16"), (128, 96, 768)),   # d = 64: three workgroups per CU
-    ((1, 8, 256 * 70, 128, False, "bf16"), (128, 64, 512)),
+    ((1, 8, 256 * 70, 128, False, "bf16"), (256, 32, 256)),  # the element type plays no part
     ((1, 1, 256 * 8 * 32, 128, False, "f16"), (256, 32, 256)),   # one head over 8 XCDs: 32 tiles each
     ((1, 1, 256 * 8 * 31, 128, False, "f16"), (128, 62, 496)),
     ((2, 3, 333, 128, False, "f16"), (128, 1, 8)),          # 6 heads: 4 parts per head, 3 tiles -> one per part
@@ -307,9 +307,7 @@ def test_variant_fields_are_validated(sa):
     with pytest.raises(binding.SawattnError) as e:
         vli(1, 8, 2048, 64, False, sa.variant(rows_per_wavefront=64))
     assert e.value.code == binding.ERR_UNSUPPORTED
-    with pytest.raises(binding.SawattnError) as e:     # 64 rows per wavefront: binary16 inputs only
-        vli(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64), dtype="bf16")
-    assert e.value.code == binding.ERR_UNSUPPORTED
+    assert vli(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64), dtype="bf16")["tile_q"] == 256
     with pytest.raises(binding.SawattnError):
         vli(1, 8, 2048, 128, False, sa.variant(rows_per_wavefront=64, slots_per_domain=33))
     with pytest.raises(binding.SawattnError):
