@@ -65,6 +65,9 @@ def parse():
                          "of K and V feed the 64-rows-per-wavefront kernel where it applies) instead of attn_fwd")
     ap.add_argument("--rows-per-wavefront", type=int, default=0, choices=[0, 32, 64],
                     help="0: what attn_fwd picks by itself; 32 or 64: that kernel shape through attn_fwd_variant")
+    ap.add_argument("--align-rounds", action="store_true",
+                    help="the workgroups of an XCD wait for each other after every round, not only between heads "
+                         "(attn_fwd_variant; a study of how much the scan order can save at best)")
     ap.add_argument("--evict", action="store_true",
                     help="overwrite a 1 GiB scratch buffer before every step so each launch starts cache-cold")
     return ap.parse_args()
@@ -181,7 +184,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype)
-    var = sa.variant(rows_per_wavefront=args.rows_per_wavefront) if args.rows_per_wavefront else None
+    var = sa.variant(rows_per_wavefront=args.rows_per_wavefront, align_rounds=int(args.align_rounds)) \
+        if (args.rows_per_wavefront or args.align_rounds) else None
     if var is not None:
         info = sa.attn_fwd_variant_launch_info(w.B, w.H, w.N, w.d, w.causal, var, w.dtype)
     ws, ws_bytes = None, 0

@@ -71,12 +71,14 @@ enum {
  * rounded to binary16 before the second contraction (for bf16 inputs V is converted to binary16 on
  * the way into LDS, which is exact for |v| in [2^-14, 65504] -- larger bf16 values of V are not
  * supported).  The caller owns every buffer.  Besides the per-thread error text the library holds
- * one piece of device state: eight 32-bit arrival counters (one per XCD) with which the workgroups
- * of an XCD wait for each other, for a bounded time, before they move on to the next head, so that
- * they keep streaming the same K/V through their shared L2.  A launch that has more than one head
- * per XCD clears them first (a one-block kernel on the same stream).  The counters steer timing
- * only: launches that overlap on one device share them, which can cost L2 hits, never correctness,
- * and no wait is unbounded.
+ * one piece of device state: eight sets of eight 32-bit arrival counters (one per XCD) with which the
+ * workgroups of an XCD wait for each other, for a bounded time, before they move on to the next
+ * head, so that they keep streaming the same K/V through their shared L2.  A launch that has more
+ * than one head per XCD takes the next set in turn and clears it first (a one-block kernel on the
+ * same stream), so launches that overlap on one device -- other streams, other host threads -- leave
+ * each other alone unless eight or more are in flight.  The counters steer timing only, never
+ * results, and no wait is unbounded: at worst (the other workgroups of an XCD not running at all, or
+ * nine overlapping launches) a workgroup waits about 8 ms at a head boundary and carries on.
  *
  * Errors: INVALID_ARG / UNSUPPORTED as listed above (nothing is launched); RUNTIME if the launch
  * fails.  Safe to call from several host threads.
@@ -118,12 +120,16 @@ typedef struct sawattn_variant {
                                 0 = default: 64 for d = 128, slots_per_domain <= 32 and sequences long enough
                                 that every workgroup of an XCD gets at least one 256-row tile of a head (two
                                 under the causal mask): ceil(ceil(N/256) / parts_per_head) >= 32 (64); else 32. */
+    int align_rounds;        /* persistent launch with the per-XCD decode: 0 = the workgroups of an XCD wait for each
+                                other between heads only (and only where they finish a head together); 1 = after
+                                every round as well, which holds them in the lockstep Sec. 3.4 assumes at a cost in
+                                time.  For measuring what the scan order can save at best.  Ignored otherwise. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round
  * over the current head (the default); persistent + linear decode: parity of the workgroup's own
  * iteration count (Alg. 4 as printed); grid launch: parity of the tile's position in its workgroup.
- * A NULL variant pointer selects { PERSISTENT, DOMAIN, 0, 0, 0 }, which is what attn_fwd runs.
+ * A NULL variant pointer selects { PERSISTENT, DOMAIN, 0, 0, 0, 0 }, which is what attn_fwd runs.
  */
 
 /*

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
@@ -77,6 +78,7 @@ struct Params {
     int negate_q;          // scale < 0: use -Q and |scale|
     int q_bf16;            // wide variant on converted inputs: Q is still bfloat16 (K and V are binary16 copies)
     int max_local;
+    int ticket_set;        // which set of arrival counters this launch uses (domain_sync)
     float c;               // |scale| * log2(e): scores are handled in the log2 domain
     Schedule sched;
 };
@@ -1310,21 +1312,25 @@ __global__ __launch_bounds__(256) void bf16_to_f16_kernel(const u4* __restrict__
 // 95 % to 55 %.  So between two heads the workgroups of a domain wait for each other on a ticket
 // counter.  The wait is bounded: if the workgroups are not all resident (a shared GPU), it gives
 // up after kSyncSpinLimit polls and the kernel carries on unaligned; results never depend on it.
-// The counters are library-owned device memory, cleared by a one-wavefront kernel enqueued before
-// every launch that uses them; launches that overlap on one GPU share them and may merely lose the
-// alignment.
-__device__ unsigned g_domain_tickets[kDomains];
-constexpr int kSyncSpinLimit = 1 << 14;
+// The counters are library-owned device memory: kTicketSets sets of one counter per domain.  Every
+// launch that uses them takes the next set in turn (a host-side count) and clears it with a
+// one-wavefront kernel enqueued just before it, so launches that overlap on one GPU -- other streams,
+// other host threads -- do not disturb each other unless kTicketSets or more of them are in flight;
+// then they may lose the alignment and wait out the bound (about 8 ms per head boundary at worst),
+// never more.
+constexpr int kTicketSets = 8;
+__device__ unsigned g_domain_tickets[kTicketSets][kDomains];
+constexpr int kSyncSpinLimit = 1 << 14;     // polls of about 1000 cycles each
 
-__global__ void clear_tickets_kernel() {
-    if (threadIdx.x < kDomains) g_domain_tickets[threadIdx.x] = 0u;
+__global__ void clear_tickets_kernel(int set) {
+    if (threadIdx.x < kDomains) g_domain_tickets[set][threadIdx.x] = 0u;
 }
 
 // Called by every workgroup of `domain` the same number of times; `slots` workgroups take part.
-__device__ __forceinline__ void domain_sync(int domain, int slots) {
+__device__ __forceinline__ void domain_sync(int set, int domain, int slots) {
     __syncthreads();
     if (threadIdx.x == 0) {
-        unsigned* t = &g_domain_tickets[domain];
+        unsigned* t = &g_domain_tickets[set][domain];
         const unsigned mine = __hip_atomic_fetch_add(t, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const unsigned target = (mine / (unsigned)slots + 1u) * (unsigned)slots;
         for (int spin = 0; spin < kSyncSpinLimit; ++spin) {
@@ -1363,7 +1369,7 @@ __global__ __launch_bounds__(kThreads, NH == 2 ? 1 : (D == 64 ? 3 : 2)) void att
         // Every workgroup of the domain comes here once per head, also those that sat rounds out.
         // (Re-aligning after every round as well brings workload 4's L2 misses down to the
         // one-miss-per-line-per-round ideal, but costs 4 % in time; between heads it is free.)
-        if (w.sync_after) domain_sync((int)blockIdx.x % kDomains, s.slots);
+        if (w.sync_after) domain_sync(p.ticket_set, (int)blockIdx.x % kDomains, s.slots);
     }
     if (p.trace_count && threadIdx.x == 0) p.trace_count[blockIdx.x] = local;
 }
@@ -1402,8 +1408,10 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
     out->max_local_tiles = s.local_iters;
 }
 
+std::atomic<unsigned> g_ticket_turn{0};
+
 template <int D, bool BF16, bool CAUSAL, int NH>
-int launch(const Params& p, int grid, hipStream_t stream) {
+int launch(Params& p, int grid, hipStream_t stream) {
     auto kern = attn_fwd_kernel<D, BF16, CAUSAL, NH>;
     constexpr int lds_bytes = NH == 2 ? kWideLdsBytes : Geo<D>::kLdsBytes;
     static thread_local bool configured = false;
@@ -1415,7 +1423,11 @@ int launch(const Params& p, int grid, hipStream_t stream) {
         }
         configured = true;
     }
-    if (p.sched.sync_heads) hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream);
+    p.ticket_set = 0;
+    if (p.sched.sync_heads || p.sched.sync_rounds) {
+        p.ticket_set = (int)(g_ticket_turn.fetch_add(1u, std::memory_order_relaxed) % (unsigned)kTicketSets);
+        hipLaunchKernelGGL(clear_tickets_kernel, dim3(1), dim3(64), 0, stream, p.ticket_set);
+    }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds_bytes, stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
@@ -1429,6 +1441,7 @@ int launch(const Params& p, int grid, hipStream_t stream) {
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
 int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out) {
     int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0;
+    bool align_rounds = false;
     if (v) {
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
@@ -1449,11 +1462,14 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
         decode = v->decode == SAWATTN_DECODE_LINEAR ? kDecodeLinear : kDecodeDomain;
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
+        if (v->align_rounds != 0 && v->align_rounds != 1)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.align_rounds must be 0 or 1");
+        align_rounds = v->align_rounds == 1;
     }
     if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
     const int tile_q = rows == 64 ? 2 * kTileQ : kTileQ;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
-    *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q);
+    *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q, align_rounds);
     return SAWATTN_OK;
 }
 

@@ -84,6 +84,7 @@ struct Schedule {
     int grid;               // workgroups launched (a multiple of kDomains)
     int local_iters;        // local iterations every workgroup runs through (some may be idle)
     int sync_heads;         // persistent, domain decode: the workgroups of a domain wait for each other between heads
+    int sync_rounds;        // ... and after every round as well (a study of Sec. 3.4's lockstep; costs time)
 };
 
 struct Work {
@@ -96,7 +97,7 @@ struct Work {
 
 // max_slots in 1..resident_slots(d), tiles_per_wg in {1, 2}; the caller has validated them.
 SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int decode, int max_slots, int tiles_per_wg,
-                              int tile_q = kTileQ) {
+                              int tile_q = kTileQ, bool align_rounds = false) {
     Schedule s;
     s.heads = heads;
     s.tile_q = tile_q;
@@ -111,6 +112,7 @@ SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int dec
     s.rounds_per_chunk = 0;
     s.units_per_chunk = 0;
     s.sync_heads = 0;
+    s.sync_rounds = 0;
     const long long total = (long long)heads * s.q_tiles;
     if (launch == kLaunchPersistent) {
         if (decode == kDecodeDomain) {
@@ -121,6 +123,7 @@ SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int dec
             // every slot gets a tile in every round, and causal tiles pair up long with short.
             const bool even_load = s.q_tiles % (s.parts * s.slots) == 0 && (!causal || s.rounds_per_chunk % 2 == 0);
             s.sync_heads = even_load && s.chunks_per_domain > 1;
+            s.sync_rounds = align_rounds && s.local_iters > 1;
         } else {
             const int want = ceil_div_i(total, kDomains);
             s.slots = want < max_slots ? want : max_slots;
@@ -164,7 +167,8 @@ SAW_HD Work decode_work(const Schedule& s, int wg, int it, bool causal, bool saw
         const int r = it - cs * s.rounds_per_chunk;
         u = r * s.slots + ((it & 1) ? s.slots - 1 - slot : slot);
         w.backward = sawtooth && (r & 1);
-        w.sync_after = s.sync_heads && r + 1 == s.rounds_per_chunk && cs + 1 < s.chunks_per_domain;
+        w.sync_after = (s.sync_heads && r + 1 == s.rounds_per_chunk && cs + 1 < s.chunks_per_domain) ||
+                       (s.sync_rounds && it + 1 < s.local_iters);
     } else {
         cs = slot / s.units_per_chunk;
         u = (slot - cs * s.units_per_chunk) * s.tiles_per_wg + it;
