@@ -223,6 +223,33 @@ def test_full_size_workloads_sampled_rows(sa, oracle, cfg):
     assert max_abs <= 2e-3 and rel <= 1e-3
 
 
+# ------------------------------------------------------------------ the shapes the sweeps report (Sec. 3.2, Sec. 4.3)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N,d", [(1, 1, 131072, 64), (1, 1, 131072, 128), (8, 1, 32768, 64)])
+def test_sweep_shapes_sampled_rows(sa, oracle, B, H, N, d, causal):
+    """The longest points of the sequence-length and batch sweeps: one head spread over all eight XCDs with
+    1024 (512) query tiles per head, several rounds per chunk, and the batch-of-eight shape.  About fifty sampled rows
+    per head against the oracle, both scan orders, plus the two orders against each other on every element."""
+    Q, K, V = workloads.make_random(B, H, N, d, "f16", seed=9000 + N + d)
+    scale = 1.0 / math.sqrt(d)
+    Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+    info = sa.attn_fwd_launch_info(B, H, N, d, causal)
+    assert info["q_tiles_per_head"] == -(-N // info["tile_q"]) and info["parts_per_head"] == 8 // math.gcd(B * H, 8)
+    outs = {}
+    for order in ORDERS:
+        outs[order] = sa.attn_fwd(Qd, Kd, Vd, scale=scale, causal=causal, scan_order=order, o_dtype=torch.float32)
+        torch.cuda.synchronize()
+    rows = sample_rows(N, 300 + d, n=40)
+    for b in sorted({0, B // 2, B - 1}):
+        want = oracle.attention(Q[b:b + 1], K[b:b + 1], V[b:b + 1], scale, causal=causal, rows=rows)[0, 0]
+        for order in ORDERS:
+            got = outs[order][b, 0][rows].double().cpu().numpy()
+            e = assert_close(got, want, f"sweep shape B{B} N{N} d{d} causal={causal} batch {b} {order}")
+            print((B, H, N, d), causal, b, order, "max-abs %.2e rel-L2 %.2e" % e, flush=True)
+    e = assert_close(outs["sawtooth"].double().cpu().numpy(), outs["cyclic"].double().cpu().numpy(),
+                     f"sweep shape B{B} N{N} d{d} causal={causal}: sawtooth vs cyclic")
+
+
 @pytest.mark.parametrize("cfg", [1, 2])
 def test_scan_orders_agree_small(sa, cfg):
     w = workloads.WORKLOADS[cfg]
@@ -258,7 +285,8 @@ def test_device_schedule_matches_oracle(sa, B, H, N, d, causal, order):
 
 # ------------------------------------------------------------------ launch variants (Alg. 2 as printed, Alg. 3, fewer slots)
 VARIANTS = [dict(decode="linear"), dict(launch="grid"), dict(launch="grid", tiles_per_workgroup=1),
-            dict(launch="grid", decode="linear"), dict(slots_per_domain=3), dict(decode="linear", slots_per_domain=7)]
+            dict(launch="grid", decode="linear"), dict(slots_per_domain=3), dict(decode="linear", slots_per_domain=7),
+            dict(align_rounds=1), dict(align_rounds=1, slots_per_domain=2)]
 
 
 @pytest.mark.parametrize("kw", VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))

@@ -300,7 +300,7 @@ def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, 
 def test_variant_fields_are_validated(sa):
     vli = sa.attn_fwd_variant_launch_info
     for bad in (dict(launch=2), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
-                dict(tiles_per_workgroup=3)):
+                dict(tiles_per_workgroup=3), dict(align_rounds=2), dict(align_rounds=-1)):
         with pytest.raises(binding.SawattnError) as e:
             vli(1, 8, 2048, 128, False, sa.variant(**bad))
         assert e.value.code == binding.ERR_INVALID_ARG and "variant." in str(e.value)
@@ -370,3 +370,26 @@ def test_byte_model_and_lru_model():
     S = 131072
     all_access = 8 * traffic_model.l2_sectors_noncausal(S, 64)
     assert all_access / 48 == pytest.approx(3.7e8, rel=0.05)
+
+
+# ------------------------------------------------------------------ the benchmark's profile figures come from profiles/
+def test_bench_reads_its_counter_figures_from_the_committed_profiles():
+    """bench.py reports HBM-side bytes and L2 misses per scan order as profile figures: they are parsed from the
+    rocprofv3 summary of the workload, so they cannot drift from it; every workload has a summary."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    from paper_2601_16032_amd import workloads
+    for k, w in workloads.WORKLOADS.items():
+        for ws in ([False, True] if k == 5 else [False]):
+            traffic, misses, rel = bench.profiled_counters(w.name, ws)
+            assert rel is not None and os.path.exists(os.path.join(ROOT, rel)), (w.name, ws)
+            text = open(os.path.join(ROOT, rel)).read()
+            for order in ("sawtooth", "cyclic"):
+                assert traffic[order] > 0 and misses[order] > 0
+                assert f"total {traffic[order]:.4e} bytes per launch" in text
+                # at least the bytes every launch has to move: Q, K, V read once
+                assert traffic[order] >= 3 * w.B * w.H * w.N * w.d * 2 * 0.5
+            assert set(traffic) == set(misses) == {"sawtooth", "cyclic"}
+    assert bench.profiled_counters("no_such_workload", False) == ({}, {}, None)
