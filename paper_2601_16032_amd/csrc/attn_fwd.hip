@@ -391,17 +391,17 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
         }
         if constexpr (WIDE) mfma_settle_v(s[0], s[1]);
     }
-    // ---- mask: keys at or beyond N, and keys after the query under the causal mask
-    unsigned masked = 0u;
+    // ---- mask: keys at or beyond N, and keys after the query under the causal mask, get the score -inf, which
+    //      c > 0 turns into the probability 0.  Register r of block b is key 32b + 8(r/4) + 4g + r%4 of the tile:
+    //      visible up to the offset `ahead` (one comparison and one select per score).
     if constexpr (MASKED) {
+        const int last_key = CAUSAL ? (qrow < N - 1 ? qrow : N - 1) : N - 1;
+        const int ahead = last_key - kv0 - 4 * g;
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kv = kv0 + 32 * b + 8 * (r >> 2) + 4 * g + (r & 3);
-                const bool m = (kv >= N) || (CAUSAL && kv > qrow);
-                if (m) { masked |= 1u << (16 * b + r); s[b][r] = -INFINITY; }
-            }
+            for (int r = 0; r < 16; ++r)
+                if (32 * b + 8 * (r >> 2) + (r & 3) > ahead) s[b][r] = -INFINITY;
     }
     // ---- online softmax in the log2 domain
     float mx = s[0][0];
@@ -433,12 +433,8 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int r = 8 * h + 2 * i;
-                float x0 = fast_exp2(__builtin_fmaf(s[b][r], c, -Mref));
-                float x1 = fast_exp2(__builtin_fmaf(s[b][r + 1], c, -Mref));
-                if constexpr (MASKED) {
-                    if ((masked >> (16 * b + r)) & 1u) x0 = 0.f;
-                    if ((masked >> (16 * b + r + 1)) & 1u) x1 = 0.f;
-                }
+                const float x0 = fast_exp2(__builtin_fmaf(s[b][r], c, -Mref));
+                const float x1 = fast_exp2(__builtin_fmaf(s[b][r + 1], c, -Mref));
                 const h2 ph = __builtin_convertvector(f2{x0, x1}, h2);
                 // running sum of the rounded probabilities, the values the second product uses
                 L = __builtin_amdgcn_fdot2(ph, ones, L, false);
@@ -891,6 +887,8 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     };
     auto set_reference = [&](int h) {
         nM[h] = -st[h].M;
+        // (c is never zero.  The select stays all the same: without it the compiler allocates this kernel's
+        // registers differently and spills around the hand-placed MFMAs.)
         lim[h] = c > 0.f ? (st[h].M + kRescaleSlack) / c : INFINITY;
     };
 
@@ -1541,7 +1539,9 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.sawtooth = scan_order == SAWATTN_SCAN_SAWTOOTH;
     p.negate_q = scale < 0.f;
     p.q_bf16 = converted;
-    p.c = (float)(std::fabs((double)scale) * 1.4426950408889634074);
+    // Never zero: the kernels mask a key by giving it the score -inf and rely on -inf * c = -inf.  At this floor
+    // every finite score times c is below 2^-60 in magnitude, so scale = 0 still gives exp2(0) = 1 for every visible key.
+    p.c = std::fmax((float)(std::fabs((double)scale) * 1.4426950408889634074), 1e-30f);
     p.sched = sched;
     p.max_local = sched.local_iters;
     const int grid = sched.grid;
