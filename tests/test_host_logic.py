@@ -393,3 +393,29 @@ def test_bench_reads_its_counter_figures_from_the_committed_profiles():
                 assert traffic[order] >= 3 * w.B * w.H * w.N * w.d * 2 * 0.5
             assert set(traffic) == set(misses) == {"sawtooth", "cyclic"}
     assert bench.profiled_counters("no_such_workload", False) == ({}, {}, None)
+
+
+def test_build_refuses_wide_kernels_that_spill():
+    """The build reads the compiler's resource remarks and refuses a library whose 64-rows-per-wavefront kernels
+    need scratch memory (their inline-assembly MFMAs are only sound without spills)."""
+    from paper_2601_16032_amd import build as hip_build
+
+    def remarks(scratch_of_one):
+        lines = []
+        for i, (bf, ca, nh) in enumerate([(0, 0, 2), (0, 1, 2), (1, 0, 2), (1, 1, 2), (0, 0, 1)]):
+            name = f"_ZN7sawattn15attn_fwd_kernelILi128ELb{bf}ELb{ca}ELi{nh}EEEvNS_6ParamsE"
+            scratch = scratch_of_one if i == 2 else (16 if nh == 1 else 0)
+            lines += [f"x.hip:1:1: remark: Function Name: {name} [-Rpass-analysis=kernel-resource-usage]",
+                      "x.hip:1:1: remark:     VGPRs: 233 [-Rpass-analysis=kernel-resource-usage]",
+                      f"x.hip:1:1: remark:     ScratchSize [bytes/lane]: {scratch} [-Rpass-analysis=kernel-resource-usage]",
+                      "x.hip:1:1: remark:     Occupancy [waves/SIMD]: 1 [-Rpass-analysis=kernel-resource-usage]"]
+        return "\n".join(lines)
+
+    res = hip_build.kernel_resources(remarks(0))
+    assert len(res) == 5
+    assert res["_ZN7sawattn15attn_fwd_kernelILi128ELb0ELb0ELi2EEEvNS_6ParamsE"] == {"VGPRs": 233, "ScratchSize": 0, "Occupancy": 1}
+    hip_build.check_wide_kernels(res)                       # 32-row kernels may spill a little, wide ones not at all
+    with pytest.raises(RuntimeError, match="must not use scratch"):
+        hip_build.check_wide_kernels(hip_build.kernel_resources(remarks(188)))
+    with pytest.raises(RuntimeError, match="expected the resource usage of 4"):
+        hip_build.check_wide_kernels({})
