@@ -87,6 +87,17 @@ def test_scale_sign_and_zero(sa, oracle):
             want = oracle.attention(Q, K, V, scale, causal=causal)
             got = run_gpu(sa, Q, K, V, scale, causal, "sawtooth", o_dtype=torch.float32)
             assert_close(got, want, f"scale={scale} causal={causal}")
+    # the same through the kernel with 64 rows per wavefront (d = 128), whose masked tiles rely on -inf scores:
+    # scale = 0 and a scale below the floor of 1e-30 on scale*log2(e) must both come out as uniform attention
+    Q, K, V = workloads.make_random(1, 2, 700, 128, "bf16", seed=6)
+    for scale in (0.0, 1e-36, -0.09):
+        for causal in (False, True):
+            want = oracle.attention(Q, K, V, scale, causal=causal)
+            for order in ORDERS:
+                O = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order,
+                                        o_dtype=torch.float32, variant=sa.variant(rows_per_wavefront=64))
+                torch.cuda.synchronize()
+                assert_close(O.double().cpu().numpy(), want, f"wide scale={scale} causal={causal} {order}")
 
 
 def test_identical_keys_uniform_attention(sa, oracle):
