@@ -23,10 +23,9 @@
 // plus, at one end, a short run of masked tiles (general_range).  The workgroups of one XCD walk
 // the same head together and re-align between heads (domain_sync).
 //
-// For head dimension 128 and binary16 inputs there is a second tile shape (NH = 2 in the templates,
-// pipelined_range_wide): a wavefront owns two such 32-row halves, a workgroup 256 query rows, one
-// workgroup per CU, every K / V^T fragment read from LDS feeds one MFMA per half, and scale*log2(e) is
-// folded into Q so that the MFMAs deliver the exponent arguments directly.
+// For head dimension 128 there is a second tile shape (NH = 2 in the templates, pipelined_range_wide):
+// a wavefront owns two such 32-row halves, a workgroup 256 query rows, one workgroup per CU, and every
+// K / V^T fragment read from LDS feeds one MFMA per half.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -207,7 +206,7 @@ __device__ __forceinline__ void tile_offsets(int j, int N, const LaneMap<D>& lm,
             const unsigned row = lm.fill_src[i] / G::kRowBytes, chunk = lm.fill_src[i] % G::kRowBytes;
             unsigned r = kv0 + row;
             r = r < (unsigned)N ? r : (unsigned)N - 1;
-            off[i] = (r - kv0) * G::kRowBytes + chunk;   // may wrap below zero: added to the tile base mod 2^32
+            off[i] = (r - kv0) * G::kRowBytes + chunk;   // (r >= kv0: tile j exists, so its first row is below N)
         }
     }
 }
@@ -792,7 +791,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
 }
 
 // ------------------------------------------------------------------------------------------------
-// Wide variant (head dimension 128, binary16 inputs): a wavefront owns 64 query rows as two 32-row
+// Wide variant (head dimension 128): a wavefront owns 64 query rows as two 32-row
 // halves, a workgroup 256 rows, one workgroup per CU.  Every K and V^T fragment read from LDS feeds
 // two MFMAs, one per half, which halves the LDS operand traffic and the L2 -> LDS traffic per flop.
 //
@@ -801,9 +800,9 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
 // (about 5 cycles per vector instruction, 9 per exponential) has to fit under those 32 cycles or the
 // pipe idles.  So the vector work per score is cut to the exponential, half a convert, half a
 // maximum and the row sum, and spread evenly over the MFMAs:
-//   * Q is multiplied by scale*log2(e) once, when the query tile is loaded, and the first MFMA of
-//     every S^T block starts from an accumulator block that holds -M (the reference maximum of the
-//     lane's query row) instead of zero, so the MFMAs deliver score - M directly;
+//   * one FMA per score (score * c - M, c = scale*log2(e) applied to the fp32 score as everywhere else); the
+//     row maximum is tracked on the raw scores against the per-row limit (M + slack) / c, so that the test
+//     "some score exceeds the slack" costs no multiply;
 //   * S^T is computed block by block (kv rows 0..31 of the tile, then 32..63): the exponentials of
 //     the second block of tile i run under the first-block MFMAs of S(i+1)^T, which do not touch it,
 //     the row sums of tile i under the second-block MFMAs; under the MFMAs of O^T += V(i)^T P(i)^T

@@ -42,10 +42,10 @@ SAW_HD int gcd_i(int a, int b) { while (b) { int t = a % b; a = b; b = t; } retu
 SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
 // Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
-// workgroup tiles) for head dimension 128 and binary16 inputs once the steady state dominates, i.e.
+// workgroup tiles) for head dimension 128 (either input type) once the steady state dominates, i.e.
 // every resident workgroup of a domain gets at least one full-length tile of a head (two under the
 // causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured break-even:
-// +7 % and more from there on, a loss below.)
+// +5 % and more from there on, a loss below.)
 SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16) {
     (void)bf16;
     if (d != 128) return 32;
