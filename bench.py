@@ -65,6 +65,9 @@ def parse():
                          "of K and V feed the 64-rows-per-wavefront kernel where it applies) instead of attn_fwd")
     ap.add_argument("--rows-per-wavefront", type=int, default=0, choices=[0, 32, 64],
                     help="0: what attn_fwd picks by itself; 32 or 64: that kernel shape through attn_fwd_variant")
+    ap.add_argument("--kv-halves", type=int, default=0, choices=[0, 1, 2],
+                    help="0: what attn_fwd picks by itself; 1: every wavefront walks the whole K/V scan; 2: 64-row tiles, "
+                         "two wavefronts per half of the scan (small unmasked fp16 problems), through attn_fwd_variant")
     ap.add_argument("--align-rounds", action="store_true",
                     help="the workgroups of an XCD wait for each other after every round, not only between heads "
                          "(attn_fwd_variant; a study of how much the scan order can save at best)")
@@ -184,8 +187,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype)
-    var = sa.variant(rows_per_wavefront=args.rows_per_wavefront, align_rounds=int(args.align_rounds)) \
-        if (args.rows_per_wavefront or args.align_rounds) else None
+    var = sa.variant(rows_per_wavefront=args.rows_per_wavefront, align_rounds=int(args.align_rounds),
+                     kv_halves=args.kv_halves) \
+        if (args.rows_per_wavefront or args.align_rounds or args.kv_halves) else None
     if var is not None:
         info = sa.attn_fwd_variant_launch_info(w.B, w.H, w.N, w.d, w.causal, var, w.dtype)
     ws, ws_bytes = None, 0
@@ -222,7 +226,8 @@ def main():
     r = res[head]
     traffic, misses, profile = profiled_counters(w.name, bool(ws_bytes)) if var is None else ({}, {}, None)
     kernel = f"attn_fwd_kernel<d={w.d}, {w.dtype if not ws_bytes else 'f16 copies'}, {'causal' if w.causal else 'full'}, " \
-             f"{info['tile_q'] // 4} rows per wavefront>"
+             + ("32 rows per wavefront, the two halves of the scan at once>" if info["tile_q"] == 64
+                else f"{info['tile_q'] // 4} rows per wavefront>")
     out = {
         "metric": "attention fwd TFLOP/s (fp16, N=16k, d=128) + L2 miss count, sawtooth vs cyclic",
         "value": r["tflops_wall"],

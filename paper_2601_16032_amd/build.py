@@ -36,11 +36,11 @@ def kernel_resources(remarks: str) -> dict:
 
 
 def check_wide_kernels(resources: dict) -> None:
-    """The kernels with 64 rows per wavefront (last template argument 2) issue their MFMAs as inline assembly with
+    """The kernels with 64 rows per wavefront (fourth template argument 2) issue their MFMAs as inline assembly with
     hand-placed wait states.  That is only sound while the compiler keeps every accumulator where the source puts
     it: a spill would copy registers that an MFMA in flight is still writing.  Refuse a build in which one of them
     needs scratch memory."""
-    wide = {k: v for k, v in resources.items() if "attn_fwd_kernel" in k and "ELi2EE" in k}
+    wide = {k: v for k, v in resources.items() if "attn_fwd_kernel" in k and "ELi2ELb" in k}
     if len(wide) != 4:
         raise RuntimeError(f"expected the resource usage of 4 kernels with 64 rows per wavefront, found {sorted(wide)}")
     bad = {k: v["ScratchSize"] for k, v in wide.items() if v.get("ScratchSize", -1) != 0}

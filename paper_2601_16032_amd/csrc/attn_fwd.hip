@@ -536,10 +536,19 @@ __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const Lane
 // two tiles ahead and V one tile ahead, still into two LDS buffers each.  For bfloat16 inputs V
 // travels global -> registers -> binary16 -> LDS, the conversion spread over the second product.
 // Self-contained like general_range().
-template <int D, bool BF16>
+//
+// HALVES: the workgroup walks two runs of `count` tiles at once -- run r = tiles j_first + (r*count + i)*step,
+// i = 0..count-1 -- for small problems, where the chip has more compute units than there are query tiles and
+// the length of one wavefront's walk is what the launch takes.  All four wavefronts fetch the tiles of both
+// runs (a second set of K/V buffers behind the first); this wavefront computes on run `run`.  binary16 inputs only.
+template <int D, bool BF16, bool HALVES = false>
 __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<D>& lm, const char* Kh, const char* Vh,
-                                                float c, int j_first, int step, int count, int lane, LDS_PTR(char) lds) {
+                                                float c, int j_first, int step, int count, int lane, LDS_PTR(char) lds,
+                                                int run = 0) {
+    static_assert(!(HALVES && BF16), "two runs at once: binary16 inputs only");
     using G = Geo<D>;
+    constexpr int RUNS = HALVES ? 2 : 1;
+    constexpr unsigned kSet = 4 * G::kTile;   // one set of buffers: K0 K1 V0 V1
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int NA = 2 * KS;            // MFMAs of one S^T tile
     constexpr int NB = 4 * DB;            // MFMAs of one O^T update
@@ -558,15 +567,24 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
     // LDS read addresses: K of the tile one ahead, V of the current tile
     unsigned rk[KS], rv[DB][2];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) rk[ks] = lds0 + lm.k_rd[ks];
+    for (int ks = 0; ks < KS; ++ks) rk[ks] = lds0 + run * kSet + lm.k_rd[ks];
 #pragma unroll
-    for (int db = 0; db < DB; ++db) { rv[db][0] = lds0 + 2 * G::kTile + lm.v_rd[db][0]; rv[db][1] = lds0 + 2 * G::kTile + lm.v_rd[db][1]; }
+    for (int db = 0; db < DB; ++db) {
+        rv[db][0] = lds0 + run * kSet + 2 * G::kTile + lm.v_rd[db][0];
+        rv[db][1] = lds0 + run * kSet + 2 * G::kTile + lm.v_rd[db][1];
+    }
 
-    auto tile_base = [&](const char* head, int i) { return head + (size_t)(j_first + i * step) * kTileKV * G::kRowBytes; };
+    // tile i of run r
+    auto tile_base = [&](const char* head, int i, int r = 0) {
+        return head + (size_t)(j_first + (r * count + i) * step) * kTileKV * G::kRowBytes;
+    };
     auto fetch_burst = [&](const char* head, int i, unsigned dst) {
-        const char* base = tile_base(head, i);
 #pragma unroll
-        for (int l = 0; l < NL; ++l) load_to_lds_16B(base, lm.fill_src[l], dst + lm.fill_dst + l * 4096);
+        for (int r = 0; r < RUNS; ++r) {
+            const char* base = tile_base(head, i, r);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) load_to_lds_16B(base, lm.fill_src[l], dst + r * kSet + lm.fill_dst + l * 4096);
+        }
     };
     auto k_read = [&](int m) -> u4 { return *(LDS_PTR(u4))(size_t)(rk[m / 2] + (m & 1) * 32 * G::kRowBytes); };
     auto v_read = [&](int idx) -> s8 {
@@ -650,6 +668,8 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
         const int cur = i & 1;
         const char* kbase = tile_base(Kh, i + 2);
         const char* vbase = tile_base(Vh, i + 1);
+        const char* kbase1 = tile_base(Kh, i + 2, RUNS - 1);   // the same tiles of the second run
+        const char* vbase1 = tile_base(Vh, i + 1, RUNS - 1);
         const unsigned kdst = lds0 + cur * G::kTile + lm.fill_dst;
         const unsigned vdst = lds0 + (2 + (cur ^ 1)) * G::kTile + lm.fill_dst;
         // ---- phase A
@@ -664,14 +684,18 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
                 A[m & 1] = mfma_16bit<BF16>(a[m], st.qf[m / 2], m < 2 ? zero : A[m & 1]);
 #pragma unroll
                 for (int q = 0; q < EU; ++q) exp_unit(m * EU + q);
-                if ((m * 2 * NL) / NA != ((m + 1) * 2 * NL) / NA) {
-                    const int li = (m * 2 * NL) / NA;
-                    if (li < NL) {
-                        if (FETCH_K) load_to_lds_16B(kbase, lm.fill_src[li], kdst + li * 4096);
+                // the fetches of an iteration, spread over its first product: K, then V (with two runs: K of
+                // both, then V of both, one load per MFMA)
+                constexpr int TL = 2 * RUNS * NL;
+                if ((m * TL) / NA != ((m + 1) * TL) / NA) {
+                    const int li = (m * TL) / NA;
+                    const int what = li / NL, l = li % NL;     // what: K run 0, (K run 1,) V run 0, (V run 1)
+                    if (what < RUNS) {
+                        if (FETCH_K) load_to_lds_16B(what ? kbase1 : kbase, lm.fill_src[l], kdst + what * kSet + l * 4096);
                     } else if constexpr (BF16) {
-                        vreg[li - NL] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[li - NL]);
+                        vreg[l] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[l]);
                     } else {
-                        load_to_lds_16B(vbase, lm.fill_src[li - NL], vdst + (li - NL) * 4096);
+                        load_to_lds_16B(what - RUNS ? vbase1 : vbase, lm.fill_src[l], vdst + (what - RUNS) * kSet + l * 4096);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -1185,13 +1209,18 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 
 // One query tile (Alg. 1 body): rows [t*128*NH, (t+1)*128*NH) of head `hh`, K/V tiles j0, j0+step, ... (nkv of
 // them).  A wavefront owns NH halves of 32 query rows each (NH = 2: the wide variant).
-template <int D, bool BF16, bool CAUSAL, int NH>
+// HALVES (32 rows per wavefront, no mask, binary16 inputs, an even number of full K/V tiles): the tile has 64 rows,
+// wavefronts 0 and 1 take them over the first half of the scan, wavefronts 2 and 3 the same rows over the second
+// half, and the two partial results are merged through LDS before the epilogue (the merge of two softmax partials:
+// common reference maximum, both rescaled to it).
+template <int D, bool BF16, bool CAUSAL, int NH, bool HALVES = false>
 __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>& lm, int hh, int t, int j0, int step,
                                                int nkv, int wave, int lane, LDS_PTR(char) lds) {
+    static_assert(!HALVES || (NH == 1 && !CAUSAL && !BF16), "two key ranges at once: 32-row kernel, no mask, binary16");
     using G = Geo<D>;
     constexpr int KS = D / 16;    // MFMA steps along d for S^T
     constexpr int DB = D / 32;    // 32-row blocks of O^T
-    constexpr int TQ = kTileQ * NH;
+    constexpr int TQ = HALVES ? kTileQ / 2 : kTileQ * NH;
     const int g = lane >> 5, ln = lane & 31;
     const int N = p.N;
     const size_t head_off = (size_t)hh * N * G::kRowBytes;
@@ -1199,7 +1228,8 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
     const char* Kh = static_cast<const char*>(p.K) + head_off;
     const char* Vh = static_cast<const char*>(p.V) + head_off;
 
-    const int qw0 = t * TQ + wave * 32 * NH;  // first query row of this wavefront
+    const int run = HALVES ? wave >> 1 : 0;                            // which half of the scan this wavefront computes
+    const int qw0 = t * TQ + (HALVES ? wave & 1 : wave) * 32 * NH;     // first query row of this wavefront
     const int qrow = qw0 + ln;                // this lane's query row in half 0 (column of S^T)
 
     TileState<D> st[NH];
@@ -1259,7 +1289,37 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             general_range<D, BF16, CAUSAL, true, NH>(st, lm2, Kh, Vh, N, c, j_first, step, n_masked, qw0, qrow, l2, lds);
         }
     };
-    if (step > 0) {
+    if constexpr (HALVES) {
+        pipelined_range<D, BF16, true>(st[0], lm, Kh, Vh, c, j0, step, nkv / 2, lane, lds, run);
+        // ---- merge: wavefront w + 2 hands (O^T, M, L) of its half to wavefront w, lane to lane, through LDS
+        //      (value k of lane l of wavefront w + 2 at float index (2k + w) * 64 + l: no bank conflicts)
+        constexpr int NV = DB * 16 + 2;
+        LDS_PTR(float) xch = (LDS_PTR(float))lds;
+        if (run == 1) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) xch[(2 * (db * 16 + r) + (wave & 1)) * 64 + lane] = st[0].o[db][r];
+            xch[(2 * (NV - 2) + (wave & 1)) * 64 + lane] = st[0].M;
+            xch[(2 * (NV - 1) + (wave & 1)) * 64 + lane] = st[0].L;
+        }
+        __syncthreads();
+        if (run == 0) {
+            const float M1 = xch[(2 * (NV - 2) + wave) * 64 + lane], L1 = xch[(2 * (NV - 1) + wave) * 64 + lane];
+            const float M = fmaxf(st[0].M, M1);
+            const float a0 = st[0].M == -INFINITY ? 0.f : fast_exp2(st[0].M - M);
+            const float a1 = M1 == -INFINITY ? 0.f : fast_exp2(M1 - M);
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    st[0].o[db][r] = st[0].o[db][r] * a0 + xch[(2 * (db * 16 + r) + wave) * 64 + lane] * a1;
+            st[0].M = M;
+            st[0].L = st[0].L * a0 + L1 * a1;
+        }
+        __syncthreads();   // the exchange area is read before the next query tile's fetches overwrite it
+        if (run == 1) return;
+    } else if (step > 0) {
         plain(j0);
         masked(j0 + n_plain * step);
     } else {
@@ -1338,8 +1398,8 @@ __device__ __forceinline__ void domain_sync(int set, int domain, int slots) {
     __syncthreads();
 }
 
-template <int D, bool BF16, bool CAUSAL, int NH>
-__global__ __launch_bounds__(kThreads, NH == 2 ? 1 : (D == 64 ? 3 : 2)) void attn_fwd_kernel(Params p) {
+template <int D, bool BF16, bool CAUSAL, int NH, bool HALVES = false>
+__global__ __launch_bounds__(kThreads, HALVES ? (D == 64 ? 2 : 1) : NH == 2 ? 1 : (D == 64 ? 3 : 2)) void attn_fwd_kernel(Params p) {
     extern __shared__ __align__(16) char smem[];
     const Schedule& s = p.sched;
     const int lane0 = threadIdx.x & 63;
@@ -1360,7 +1420,7 @@ __global__ __launch_bounds__(kThreads, NH == 2 ? 1 : (D == 64 ? 3 : 2)) void att
             int lane = lane0;
             asm volatile("" : "+v"(lane));
             const LaneMap<D> lm(wave, lane);
-            process_q_tile<D, BF16, CAUSAL, NH>(p, lm, w.head, w.tile, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
+            process_q_tile<D, BF16, CAUSAL, NH, HALVES>(p, lm, w.head, w.tile, j0, step, nkv, wave, lane, (LDS_PTR(char))smem);
             ++local;
         }
         // Every workgroup of the domain comes here once per head, also those that sat rounds out.
@@ -1397,7 +1457,8 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
     out->tile_kv = kTileKV;
     out->block_threads = kThreads;
     out->grid = s.grid;
-    out->lds_bytes = s.tile_q > kTileQ ? kWideLdsBytes : (d == 128 ? Geo<128>::kLdsBytes : Geo<64>::kLdsBytes);
+    out->lds_bytes = s.tile_q > kTileQ ? kWideLdsBytes
+                                       : (s.tile_q < kTileQ ? 2 : 1) * (d == 128 ? Geo<128>::kLdsBytes : Geo<64>::kLdsBytes);
     out->domains = kDomains;
     out->slots = s.slots;
     out->parts_per_head = s.parts;
@@ -1407,10 +1468,10 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
 
 std::atomic<unsigned> g_ticket_turn{0};
 
-template <int D, bool BF16, bool CAUSAL, int NH>
+template <int D, bool BF16, bool CAUSAL, int NH, bool HALVES = false>
 int launch(Params& p, int grid, hipStream_t stream) {
-    auto kern = attn_fwd_kernel<D, BF16, CAUSAL, NH>;
-    constexpr int lds_bytes = NH == 2 ? kWideLdsBytes : Geo<D>::kLdsBytes;
+    auto kern = attn_fwd_kernel<D, BF16, CAUSAL, NH, HALVES>;
+    constexpr int lds_bytes = NH == 2 ? kWideLdsBytes : (HALVES ? 2 : 1) * Geo<D>::kLdsBytes;
     static thread_local bool configured = false;
     if (!configured) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1437,9 +1498,19 @@ int launch(Params& p, int grid, hipStream_t stream) {
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
 int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out) {
-    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0;
+    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0, halves = 0;
     bool align_rounds = false;
     if (v) {
+        if (v->kv_halves < 0 || v->kv_halves > 2)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.kv_halves must be 0 (default), 1 or 2");
+        halves = v->kv_halves;
+        if (halves == 2) {
+            if (causal || bf16 || N % (2 * kTileKV) != 0)
+                return fail(SAWATTN_ERR_UNSUPPORTED,
+                            "variant.kv_halves = 2 needs binary16 inputs, no causal mask and N a multiple of 128");
+            if (v->rows_per_wavefront == 64)
+                return fail(SAWATTN_ERR_UNSUPPORTED, "variant.kv_halves = 2 goes with 32 rows per wavefront");
+        }
         if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
         if (v->decode != SAWATTN_DECODE_DOMAIN && v->decode != SAWATTN_DECODE_LINEAR)
@@ -1449,10 +1520,14 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
         if (v->rows_per_wavefront == 64 && d != 128)
             return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
         rows = v->rows_per_wavefront;
+        if (halves == 0) halves = rows == 64 ? 1 : default_kv_halves(B * H, N, causal, bf16);
+        if (halves == 2) rows = 32;
         if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16);
-        if (v->slots_per_domain < 0 || v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : kTileQ))
+        if (v->slots_per_domain < 0 ||
+            v->slots_per_domain > resident_slots(d, rows == 64 ? 2 * kTileQ : (halves == 2 ? kTileQ / 2 : kTileQ)))
             return fail(SAWATTN_ERR_INVALID_ARG,
-                        "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per wavefront)");
+                        "variant.slots_per_domain must be 0 (default) or 1..64 (1..96 for d = 64, 1..32 with 64 rows per "
+                        "wavefront; with kv_halves = 2: 1..64 for d = 64, 1..32 for d = 128)");
         if (v->tiles_per_workgroup < 0 || v->tiles_per_workgroup > 2)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.tiles_per_workgroup must be 0 (default), 1 or 2");
         launch = v->launch == SAWATTN_LAUNCH_GRID ? kLaunchGrid : kLaunchPersistent;
@@ -1463,8 +1538,10 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.align_rounds must be 0 or 1");
         align_rounds = v->align_rounds == 1;
     }
+    if (halves == 0) halves = default_kv_halves(B * H, N, causal, bf16);
+    if (halves == 2) rows = 32;
     if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
-    const int tile_q = rows == 64 ? 2 * kTileQ : kTileQ;
+    const int tile_q = rows == 64 ? 2 * kTileQ : (halves == 2 ? kTileQ / 2 : kTileQ);
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q, align_rounds);
     return SAWATTN_OK;
@@ -1562,6 +1639,8 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         if (bf && !converted) return ca ? launch<128, true, true, 2>(p, grid, stream) : launch<128, true, false, 2>(p, grid, stream);
         return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
+    if (sched.tile_q < kTileQ)   // 64-row tiles: the two halves of the K/V scan at once (binary16, no mask)
+        return d == 128 ? launch<128, false, false, 1, true>(p, grid, stream) : launch<64, false, false, 1, true>(p, grid, stream);
     if (d == 128) {
         if (bf) return ca ? launch<128, true, true, 1>(p, grid, stream) : launch<128, true, false, 1>(p, grid, stream);
         return ca ? launch<128, false, true, 1>(p, grid, stream) : launch<128, false, false, 1>(p, grid, stream);
@@ -1720,7 +1799,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in
 }
 
 const char* attn_last_error(void) { return sawattn::g_err; }
-int attn_version(void) { return 200; }
+int attn_version(void) { return 210; }
 const char* sawattn_last_error(void) { return attn_last_error(); }
 int sawattn_version(void) { return attn_version(); }
 

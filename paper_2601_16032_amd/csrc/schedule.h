@@ -57,7 +57,22 @@ SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool
 // Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head
 // dimension of 64 leaves room for three (168 VGPRs per wavefront, 32 KiB LDS per workgroup), 128 for
 // two; the wide variant (256-row tiles, up to 512 registers per wavefront, 128 KiB LDS) runs one.
-SAW_HD int resident_slots(int d, int tile_q = kTileQ) { return tile_q > kTileQ ? 32 : (d == 64 ? 96 : 64); }
+// With 64-row tiles (the two halves of a scan at once, twice the LDS) two fit at d = 64 and one at d = 128.
+SAW_HD int resident_slots(int d, int tile_q = kTileQ) {
+    if (tile_q > kTileQ) return 32;
+    if (tile_q < kTileQ) return d == 64 ? 64 : 32;
+    return d == 64 ? 96 : 64;
+}
+
+// Small problems: when the 128-row query tiles of the whole problem occupy at most half of the 256 compute units,
+// the launch takes as long as one wavefront needs to walk all K/V tiles of a head.  Then a workgroup takes 64 rows
+// instead and walks the two halves of the scan at once, two wavefronts each (no mask, binary16 inputs, an even
+// number of full K/V tiles).  1 = one scan per workgroup, 2 = two halves.
+SAW_HD int default_kv_halves(int heads, int N, bool causal, bool bf16) {
+    if (causal || bf16 || N % (2 * kTileKV) != 0) return 1;
+    const long long tiles = (long long)heads * ((N + kTileQ - 1) / kTileQ);
+    return tiles <= 128 ? 2 : 1;
+}
 
 // Besides that default, the launch variants the paper describes are kept selectable so that they
 // can be measured against it: the literal global stride of Alg. 2 (workgroup k takes the linear

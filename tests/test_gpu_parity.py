@@ -531,3 +531,67 @@ def test_workspace_path_at_full_size(sa, oracle):
             e = assert_close(O[b, h][rows].double().cpu().numpy(), wants[(b, h)], f"workload 5 workspace {order} ({b},{h})")
             print("workspace", (b, h), order, "max-abs %.2e rel-L2 %.2e" % e, flush=True)
         assert_close(O[0, :4].double().cpu().numpy(), plain[0, :4].double().cpu().numpy(), f"workspace vs plain {order}")
+
+
+# ------------------------------------------------------------------ the two halves of the K/V scan at once (small problems)
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("B,H,N,d,kw", [
+    (1, 1, 256, 64, {}), (1, 8, 2048, 64, {}), (2, 3, 384, 128, {}), (1, 5, 1280, 128, {}),
+    (1, 8, 2048, 64, dict(slots_per_domain=3)),              # several rounds per head: both directions
+    (1, 4, 1024, 128, dict(launch="grid")), (1, 6, 640, 64, dict(decode="linear", slots_per_domain=2)),
+    (1, 16, 4096, 64, {}),                                    # not what attn_fwd would pick by itself: 512 tiles
+])
+def test_halved_scan_every_element(sa, oracle, B, H, N, d, kw, order):
+    """kv_halves = 2: 64-row tiles, wavefronts 0-1 over the first half of the keys, 2-3 over the second, merged before
+    the epilogue.  Every element against the oracle, the recorded schedule against the schedule oracle, and the
+    single-scan kernel on the same inputs for comparison."""
+    Q, K, V = workloads.make_random(B, H, N, d, "f16", seed=77 + N)
+    scale = 1.0 / math.sqrt(d)
+    want = oracle.attention(Q, K, V, scale, causal=False)
+    var = sa.variant(kv_halves=2, **kw)
+    info = sa.attn_fwd_variant_launch_info(B, H, N, d, False, var)
+    assert info["tile_q"] == 64
+    O, trace, count = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=False, scan_order=order,
+                                          o_dtype=torch.float32, variant=var, trace=True)
+    torch.cuda.synchronize()
+    assert_close(O.double().cpu().numpy(), want, f"halved scan {B},{H},{N},{d} {kw} {order}")
+    from oracle import schedule_oracle as so
+    sched = so.schedule(B, H, N, False, order, **oracle_inputs(info, d, kw))
+    trace, count = trace.cpu(), count.cpu()
+    assert trace.shape[0] == len(sched)
+    for wg in range(info["grid"]):
+        assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == sched[wg], f"workgroup {wg}"
+    one = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=False, scan_order=order,
+                              o_dtype=torch.float32, variant=sa.variant(kv_halves=1, **kw))
+    torch.cuda.synchronize()
+    assert_close(O.double().cpu().numpy(), one.double().cpu().numpy(), "halved against single scan")
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_halved_scan_merges_halves_with_different_maxima(sa, oracle, d):
+    """Score levels that differ by tens of binades between the two halves of the keys (either way round, and
+    per head), so that the merge has to rescale one partial result by a very small factor; negative scale too."""
+    H, N = 6, 1024
+    g = torch.Generator("cpu").manual_seed(99 + d)
+    level = 40.0 * torch.rand(H, N // 64, generator=g)
+    level[:3, : N // 128] += 45.0        # heads 0-2: the first half of the keys dominates
+    level[3:, N // 128:] += 45.0         # heads 3-5: the second half
+    K = torch.randn(1, H, N, d, generator=g)
+    K[0, :, :, 0] = level.repeat_interleave(64, dim=1)
+    Q = 0.3 * torch.randn(1, H, N, d, generator=g)
+    Q[0, :, :, 0] = 4.0
+    V = torch.randn(1, H, N, d, generator=g)
+    Q, K, V = Q.half(), K.half(), V.half()
+    for scale in (1.0, -0.5):
+        want = oracle.attention(Q, K, V, scale, causal=False)
+        for order in ORDERS:
+            O = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=False, scan_order=order,
+                                    o_dtype=torch.float32, variant=sa.variant(kv_halves=2))
+            torch.cuda.synchronize()
+            assert_close(O.double().cpu().numpy(), want, f"halves with different maxima d={d} scale={scale} {order}")
+
+
+def test_halved_scan_is_what_the_small_workloads_run(sa):
+    for cfg in (1, 2):
+        w = workloads.WORKLOADS[cfg]
+        assert sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, "sawtooth", w.dtype)["tile_q"] == 64

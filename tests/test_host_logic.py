@@ -209,8 +209,14 @@ def test_schedule_oracle_hand_example_wide_tiles():
 # 256-row tiles (128 KiB LDS, 512 registers).  256-row tiles where the measured break-even says so: d = 128,
 # at least 32 such tiles of a head per XCD (64 under the causal mask).
 KERNEL_CHOICE = [
-    ((1, 1, 256, 64, False, "f16"), (128, 1, 8)),           # workload 1: two tiles, one head over 8 XCDs
-    ((1, 8, 2048, 64, False, "f16"), (128, 16, 128)),       # workload 2: 16 tiles per head, one head per XCD
+    ((1, 1, 256, 64, False, "f16"), (64, 1, 8)),            # workload 1: four 64-row tiles, one head over 8 XCDs
+    ((1, 8, 2048, 64, False, "f16"), (64, 32, 256)),        # workload 2: 32 tiles of 64 rows per head, one head per XCD
+    ((1, 8, 2048, 64, True, "f16"), (128, 16, 128)),        # ... the halved scan is for unmasked binary16 problems only
+    ((1, 8, 2048, 64, False, "bf16"), (128, 16, 128)),
+    ((1, 8, 2048 + 64, 64, False, "f16"), (128, 17, 136)),  # ... with an even number of full K/V tiles
+    ((1, 16, 1024, 128, False, "f16"), (64, 16, 128)),      # 128 tiles of 128 rows: still at most half the CUs (two
+                                                            # heads per XCD, one after the other, 16 tiles of 64 rows each)
+    ((1, 17, 1024, 128, False, "f16"), (128, 1, 8)),        # 136 tiles: no longer (17 heads: 8 parts of one tile per head)
     ((1, 16, 8192, 128, True, "bf16"), (128, 64, 512)),     # workload 3
     ((1, 32, 16384, 128, False, "f16"), (256, 32, 256)),    # workload 4: 64 tiles of 256 rows per head
     ((4, 32, 32768, 128, True, "bf16"), (256, 32, 256)),    # workload 5: 128 tiles of 256 rows per head
@@ -234,7 +240,10 @@ def test_kernel_choice_by_hand_listed_cases(sa, shape, want):
     assert info == sa.attn_fwd_launch_info(B, H, N, d, causal, "cyclic", dtype)     # the order plays no part
     assert info == sa.attn_fwd_variant_launch_info(B, H, N, d, causal, None, dtype)
     assert info["tile_kv"] == 64 and info["block_threads"] == 256 and info["domains"] == 8
-    assert info["lds_bytes"] == {(128, 128): 65536, (128, 64): 32768, (256, 128): 131072}[(info["tile_q"], d)]
+    # 8 KiB per K/V tile at d = 64, 16 at d = 128: two K and two V buffers; four each with 256-row tiles; two sets of
+    # two each with 64-row tiles (the two halves of the scan at once)
+    assert info["lds_bytes"] == {(128, 128): 65536, (128, 64): 32768, (256, 128): 131072, (64, 64): 65536,
+                                 (64, 128): 131072}[(info["tile_q"], d)]
     # a request for more workgroups per XCD than fit with 256-row tiles keeps 128-row tiles
     if want[0] == 256:
         assert sa.attn_fwd_variant_launch_info(B, H, N, d, causal, sa.variant(slots_per_domain=64), dtype)["tile_q"] == 128
@@ -263,7 +272,7 @@ def test_host_plan_matches_schedule_oracle(sa, B, H, N, causal, order):
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
-    var = sa.variant(**kw)
+    var = sa.variant(kv_halves=1, **kw)      # 128-row tiles also where the default would halve the scan
     info = sa.attn_fwd_variant_launch_info(B, H, N, 64, causal, var)
     geo = so.launch_geometry(B, H, N, **oracle_kw(kw))
     assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"]
@@ -276,11 +285,52 @@ def test_host_plan_of_variants_matches_schedule_oracle(sa, B, H, N, causal, kw):
             assert got == want[wg], f"workgroup {wg} {order}"
 
 
+@pytest.mark.parametrize("kw", [dict(), dict(launch="grid"), dict(decode="linear", slots_per_domain=3)],
+                         ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()) or "default")
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("B,H,N", [(1, 1, 256), (1, 8, 2048), (2, 3, 384), (1, 32, 16384)])
+def test_host_plan_with_halved_scan_matches_schedule_oracle(sa, B, H, N, d, kw):
+    """kv_halves = 2: 64-row tiles, two workgroups per CU at d = 64 and one at d = 128 (hand-listed in util.py);
+    the work decode is the same function of the tile height as everywhere else."""
+    var = sa.variant(kv_halves=2, **kw)
+    info = sa.attn_fwd_variant_launch_info(B, H, N, d, False, var)
+    assert info["tile_q"] == 64 and info["lds_bytes"] == (65536 if d == 64 else 131072)
+    okw = oracle_inputs(info, d, kw)
+    assert okw["resident"] == kw.get("slots_per_domain", 64 if d == 64 else 32)
+    geo = so.launch_geometry(B, H, N, **okw)
+    assert info["grid"] == geo["grid"] and info["slots"] == geo["slots"] and info["max_local_tiles"] == geo["max_local"]
+    for order in ("cyclic", "sawtooth"):
+        trace, count = sa.attn_fwd_plan(B, H, N, d, False, order, var)
+        want = so.schedule(B, H, N, False, order, **okw)
+        for wg in range(info["grid"]):
+            assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == want[wg], f"workgroup {wg} {order}"
+
+
+def test_halved_scan_is_refused_where_it_does_not_apply(sa):
+    for args, kw in (((1, 8, 2048, 64, True), dict(kv_halves=2)),                       # causal mask
+                     ((1, 8, 2048 + 64, 64, False), dict(kv_halves=2)),                 # odd number of K/V tiles
+                     ((1, 8, 2000, 64, False), dict(kv_halves=2)),                      # ragged last tile
+                     ((1, 8, 2048, 128, False), dict(kv_halves=2, rows_per_wavefront=64))):
+        with pytest.raises(sa.SawattnError) as e:
+            sa.attn_fwd_variant_launch_info(*args, sa.variant(**kw))
+        assert e.value.code == sa.ERR_UNSUPPORTED
+    with pytest.raises(sa.SawattnError) as e:
+        sa.attn_fwd_variant_launch_info(1, 8, 2048, 64, False, sa.variant(kv_halves=2), "bf16")
+    assert e.value.code == sa.ERR_UNSUPPORTED
+    for bad in (-1, 3):
+        with pytest.raises(sa.SawattnError) as e:
+            sa.attn_fwd_variant_launch_info(1, 8, 2048, 64, False, sa.variant(kv_halves=bad))
+        assert e.value.code == sa.ERR_INVALID_ARG
+    # kv_halves = 1 keeps 128-row tiles where the default would halve
+    assert sa.attn_fwd_variant_launch_info(1, 8, 2048, 64, False, sa.variant(kv_halves=1))["tile_q"] == 128
+    assert sa.attn_fwd_launch_info(1, 8, 2048, 64, False)["tile_q"] == 64
+
+
 @pytest.mark.parametrize("kw", WIDE_VARIANTS, ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()))
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N", SHAPES)
 def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, causal, kw):
-    var = sa.variant(**kw)
+    var = sa.variant(kv_halves=1, **kw)      # (32 rows per wavefront is also what the halved scan runs, on 64-row tiles)
     info = sa.attn_fwd_variant_launch_info(B, H, N, 128, causal, var)
     rows = kw["rows_per_wavefront"]
     okw = oracle_kw(kw, tile_q=4 * rows, resident=32 if rows == 64 else 64)
@@ -403,7 +453,7 @@ def test_build_refuses_wide_kernels_that_spill():
     def remarks(scratch_of_one):
         lines = []
         for i, (bf, ca, nh) in enumerate([(0, 0, 2), (0, 1, 2), (1, 0, 2), (1, 1, 2), (0, 0, 1)]):
-            name = f"_ZN7sawattn15attn_fwd_kernelILi128ELb{bf}ELb{ca}ELi{nh}EEEvNS_6ParamsE"
+            name = f"_ZN7sawattn15attn_fwd_kernelILi128ELb{bf}ELb{ca}ELi{nh}ELb0EEEvNS_6ParamsE"
             scratch = scratch_of_one if i == 2 else (16 if nh == 1 else 0)
             lines += [f"x.hip:1:1: remark: Function Name: {name} [-Rpass-analysis=kernel-resource-usage]",
                       "x.hip:1:1: remark:     VGPRs: 233 [-Rpass-analysis=kernel-resource-usage]",
@@ -413,7 +463,7 @@ def test_build_refuses_wide_kernels_that_spill():
 
     res = hip_build.kernel_resources(remarks(0))
     assert len(res) == 5
-    assert res["_ZN7sawattn15attn_fwd_kernelILi128ELb0ELb0ELi2EEEvNS_6ParamsE"] == {"VGPRs": 233, "ScratchSize": 0, "Occupancy": 1}
+    assert res["_ZN7sawattn15attn_fwd_kernelILi128ELb0ELb0ELi2ELb0EEEvNS_6ParamsE"] == {"VGPRs": 233, "ScratchSize": 0, "Occupancy": 1}
     hip_build.check_wide_kernels(res)                       # 32-row kernels may spill a little, wide ones not at all
     with pytest.raises(RuntimeError, match="must not use scratch"):
         hip_build.check_wide_kernels(hip_build.kernel_resources(remarks(188)))

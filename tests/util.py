@@ -26,9 +26,10 @@ def assert_close(got, want, what=""):
 
 # Workgroups of one XCD that run at the same time, by (head dimension, query rows per workgroup tile): 32 CUs times
 # the workgroups a CU holds (three at d = 64: 32 KiB LDS and at most 168 registers each; two at d = 128; one with
-# 256-row tiles, which take 128 KiB LDS and 512 registers per wavefront).  Listed here by hand: the schedule oracle
-# takes it as an input and the library's own figure is compared with it.
-RESIDENT_PER_XCD = {(64, 128): 96, (128, 128): 64, (128, 256): 32}
+# 256-row tiles, which take 128 KiB LDS and 512 registers per wavefront; with 64-row tiles -- the two halves of the
+# K/V scan at once, twice the LDS of a 128-row tile -- two at d = 64 and one at d = 128).  Listed here by hand: the
+# schedule oracle takes it as an input and the library's own figure is compared with it.
+RESIDENT_PER_XCD = {(64, 128): 96, (128, 128): 64, (128, 256): 32, (64, 64): 64, (128, 64): 32}
 
 
 def oracle_inputs(info, d, variant_kw=None):
