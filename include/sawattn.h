@@ -94,8 +94,13 @@ int attn_fwd(const void* Q, const void* K, const void* V, void* O,
  */
 enum {
     SAWATTN_LAUNCH_PERSISTENT = 0, /* Alg. 2: a fixed set of workgroups loops over the query tiles */
-    SAWATTN_LAUNCH_GRID = 1        /* Alg. 3: one workgroup per `tiles_per_workgroup` consecutive query
+    SAWATTN_LAUNCH_GRID = 1,       /* Alg. 3: one workgroup per `tiles_per_workgroup` consecutive query
                                       tiles, handed to the hardware dispatcher */
+    SAWATTN_LAUNCH_AUTO = 2        /* what attn_fwd does: PERSISTENT, except where a head has fewer query tiles than
+                                      an XCD holds workgroups and an XCD has three or more heads (two without the
+                                      causal mask) to go through -- then GRID with one tile per workgroup, so that
+                                      the tiles of several heads run side by side (with slots_per_domain or the
+                                      linear decode given: PERSISTENT) */
 };
 enum {
     SAWATTN_DECODE_DOMAIN = 0,     /* work is dealt out per XCD (one L2 each): the workgroups of an XCD
@@ -105,14 +110,14 @@ enum {
                                       persistent workgroup k takes k, k+G, k+2G, ... */
 };
 typedef struct sawattn_variant {
-    int launch;              /* SAWATTN_LAUNCH_* */
+    int launch;              /* SAWATTN_LAUNCH_* (0 = PERSISTENT; attn_fwd itself runs AUTO) */
     int decode;              /* SAWATTN_DECODE_* */
     int slots_per_domain;    /* persistent launch: at most this many workgroups per XCD, so G = 8 * slots
                                 (Sec. 3.4's resident-CTA sweep): 1..64, or 1..96 for d = 64, where three
                                 workgroups fit a CU; 0 = default (that maximum).  Ignored by the grid launch. */
     int tiles_per_workgroup; /* grid launch: 1, or 2 = forward over the first tile and, with the sawtooth
                                 order, backward over the second (Sec. 4.3's step-2 alternation);
-                                0 = default (2).  Ignored by the persistent launch. */
+                                0 = default (2; 1 where AUTO picks the grid launch).  Ignored by the persistent launch. */
     int rows_per_wavefront;  /* 32: a workgroup takes 128 query rows (two or three workgroups per CU);
                                 64 (d = 128 only; UNSUPPORTED otherwise): 256 rows, one workgroup per CU (at
                                 most 32 per XCD), every K/V fragment read from LDS feeds two MFMAs; same
@@ -169,6 +174,8 @@ typedef struct sawattn_launch_info {
     int parts_per_head;    /* domains that share one head's query tiles (1 when B*H % 8 == 0) */
     int q_tiles_per_head;  /* ceil(N / tile_q) */
     int max_local_tiles;   /* most query tiles any one workgroup processes */
+    int launch;            /* SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID: which of the two runs */
+    int tiles_per_workgroup; /* grid launch: consecutive query tiles per workgroup (1 with the persistent launch) */
 } sawattn_launch_info;
 
 /*

@@ -16,7 +16,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_RUNTIME = 0, 1, 2, 3
 SCAN_CYCLIC, SCAN_SAWTOOTH = 0, 1
 F16, BF16, F32 = 0, 1, 2
 
-LAUNCH_PERSISTENT, LAUNCH_GRID = 0, 1
+LAUNCH_PERSISTENT, LAUNCH_GRID, LAUNCH_AUTO = 0, 1, 2
 DECODE_DOMAIN, DECODE_LINEAR = 0, 1
 
 _DTYPE_CODE = {torch.float16: F16, torch.bfloat16: BF16, torch.float32: F32}
@@ -27,7 +27,7 @@ _SCAN_CODE = {"cyclic": SCAN_CYCLIC, "sawtooth": SCAN_SAWTOOTH, SCAN_CYCLIC: SCA
 class LaunchInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in (
         "tile_q", "tile_kv", "block_threads", "grid", "lds_bytes", "domains", "slots",
-        "parts_per_head", "q_tiles_per_head", "max_local_tiles")]
+        "parts_per_head", "q_tiles_per_head", "max_local_tiles", "launch", "tiles_per_workgroup")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -40,7 +40,7 @@ class Variant(ctypes.Structure):
                 ("align_rounds", ctypes.c_int), ("kv_halves", ctypes.c_int)]
 
 
-_LAUNCH_CODE = {"persistent": LAUNCH_PERSISTENT, "grid": LAUNCH_GRID}
+_LAUNCH_CODE = {"persistent": LAUNCH_PERSISTENT, "grid": LAUNCH_GRID, "auto": LAUNCH_AUTO}
 _DECODE_CODE = {"domain": DECODE_DOMAIN, "linear": DECODE_LINEAR}
 
 

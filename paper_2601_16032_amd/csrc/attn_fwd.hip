@@ -1464,6 +1464,8 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
     out->parts_per_head = s.parts;
     out->q_tiles_per_head = s.q_tiles;
     out->max_local_tiles = s.local_iters;
+    out->launch = s.launch == kLaunchGrid ? SAWATTN_LAUNCH_GRID : SAWATTN_LAUNCH_PERSISTENT;
+    out->tiles_per_workgroup = s.tiles_per_wg;
 }
 
 std::atomic<unsigned> g_ticket_turn{0};
@@ -1498,7 +1500,7 @@ int launch(Params& p, int grid, hipStream_t stream) {
 
 // Validates a variant description (NULL = the default schedule) and builds its schedule.
 int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawattn_variant* v, Schedule* out) {
-    int launch = kLaunchPersistent, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 2, rows = 0, halves = 0;
+    int launch = -1 /* chosen below */, decode = kDecodeDomain, max_slots = 0, tiles_per_wg = 0, rows = 0, halves = 0;
     bool align_rounds = false;
     if (v) {
         if (v->kv_halves < 0 || v->kv_halves > 2)
@@ -1511,8 +1513,9 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             if (v->rows_per_wavefront == 64)
                 return fail(SAWATTN_ERR_UNSUPPORTED, "variant.kv_halves = 2 goes with 32 rows per wavefront");
         }
-        if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID)
-            return fail(SAWATTN_ERR_INVALID_ARG, "variant.launch must be SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID");
+        if (v->launch != SAWATTN_LAUNCH_PERSISTENT && v->launch != SAWATTN_LAUNCH_GRID && v->launch != SAWATTN_LAUNCH_AUTO)
+            return fail(SAWATTN_ERR_INVALID_ARG,
+                        "variant.launch must be SAWATTN_LAUNCH_PERSISTENT, SAWATTN_LAUNCH_GRID or SAWATTN_LAUNCH_AUTO");
         if (v->decode != SAWATTN_DECODE_DOMAIN && v->decode != SAWATTN_DECODE_LINEAR)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.decode must be SAWATTN_DECODE_DOMAIN or SAWATTN_DECODE_LINEAR");
         if (v->rows_per_wavefront != 0 && v->rows_per_wavefront != 32 && v->rows_per_wavefront != 64)
@@ -1530,7 +1533,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
                         "wavefront; with kv_halves = 2: 1..64 for d = 64, 1..32 for d = 128)");
         if (v->tiles_per_workgroup < 0 || v->tiles_per_workgroup > 2)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.tiles_per_workgroup must be 0 (default), 1 or 2");
-        launch = v->launch == SAWATTN_LAUNCH_GRID ? kLaunchGrid : kLaunchPersistent;
+        if (v->launch != SAWATTN_LAUNCH_AUTO) launch = v->launch == SAWATTN_LAUNCH_GRID ? kLaunchGrid : kLaunchPersistent;
         decode = v->decode == SAWATTN_DECODE_LINEAR ? kDecodeLinear : kDecodeDomain;
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
@@ -1542,6 +1545,12 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
     if (halves == 2) rows = 32;
     if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
     const int tile_q = rows == 64 ? 2 * kTileQ : (halves == 2 ? kTileQ / 2 : kTileQ);
+    if (launch < 0) {
+        // the caller leaves the launch open: persistent, or for short heads the direct launch with one tile each
+        launch = decode == kDecodeDomain && max_slots == 0 ? default_launch(B * H, N, d, causal, tile_q) : kLaunchPersistent;
+        if (launch == kLaunchGrid && tiles_per_wg == 0) tiles_per_wg = 1;
+    }
+    if (tiles_per_wg == 0) tiles_per_wg = 2;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q, align_rounds);
     return SAWATTN_OK;

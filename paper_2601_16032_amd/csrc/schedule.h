@@ -81,6 +81,23 @@ SAW_HD int default_kv_halves(int heads, int N, bool causal, bool bf16) {
 // Alg. 3 with one workgroup per one or two consecutive query tiles, where the second tile is
 // walked backward (the step-2 alternation of Sec. 4.3).
 enum { kLaunchPersistent = 0, kLaunchGrid = 1 };
+
+// Launch when the caller leaves the choice open.  The persistent hand-out gives one head at a time to the
+// workgroups of an XCD, which is what keeps a long head's K/V in one L2; a head with fewer query tiles than the
+// XCD holds workgroups then leaves compute units idle, and with several such heads per XCD one after the other
+// the launch takes several times longer than it has to (B*H = 128, N = 512, d = 64: 140 us against 17 us).  There
+// the direct launch of Alg. 3 with one tile per workgroup is taken: the hardware dispatcher runs the tiles of all
+// heads of an XCD side by side, still head by head in workgroup order.  Not for one or two causal heads per XCD,
+// where the persistent hand-out pairs a long tile with a short one per workgroup and the dispatcher cannot.
+SAW_HD int default_launch(int heads, int N, int d, bool causal, int tile_q) {
+    const int parts = kDomains / gcd_i(heads, kDomains);
+    const int q_tiles = (N + tile_q - 1) / tile_q;
+    const int per_part = (q_tiles + parts - 1) / parts;
+    const long long chunks = ((long long)heads * parts) / kDomains;
+    const int resident = tile_q > kTileQ ? 32 : (tile_q < kTileQ ? (d == 64 ? 64 : 32) : (d == 64 ? 96 : 64));
+    if (per_part >= resident) return kLaunchPersistent;
+    return chunks >= 3 || (!causal && chunks >= 2) ? kLaunchGrid : kLaunchPersistent;
+}
 enum { kDecodeDomain = 0, kDecodeLinear = 1 };
 
 struct Schedule {

@@ -595,3 +595,36 @@ def test_halved_scan_is_what_the_small_workloads_run(sa):
     for cfg in (1, 2):
         w = workloads.WORKLOADS[cfg]
         assert sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, "sawtooth", w.dtype)["tile_q"] == 64
+
+
+# ------------------------------------------------------------------ short heads, several per XCD: attn_fwd launches one workgroup per tile
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("B,H,N,d,dtype,causal", [
+    (1, 128, 512, 64, "f16", False), (2, 32, 1024, 64, "bf16", True), (1, 17, 1024, 128, "f16", False),
+    (1, 40, 1000, 128, "bf16", True), (3, 8, 700, 64, "f16", True), (1, 16, 4096, 64, "f16", False),
+])
+def test_short_heads_run_side_by_side(sa, oracle, B, H, N, d, dtype, causal, order):
+    """Where a head has fewer query tiles than an XCD holds workgroups and an XCD has several heads, attn_fwd takes
+    the direct launch (Alg. 3, one tile per workgroup).  Every element (sampled rows for the largest) against the
+    oracle, and the recorded schedule against the schedule oracle."""
+    info = sa.attn_fwd_launch_info(B, H, N, d, causal, order, dtype)
+    assert info["launch"] == sa.LAUNCH_GRID and info["tiles_per_workgroup"] == 1
+    Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=500 + H)
+    scale = 1.0 / math.sqrt(d)
+    rows = None if B * H * N <= 70000 else list(range(0, N, 37)) + [N - 1]
+    want = oracle.attention(Q, K, V, scale, causal=causal, rows=rows)
+    O, trace, count = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order,
+                                          o_dtype=torch.float32, variant=None, trace=True)
+    torch.cuda.synchronize()
+    got = O.double().cpu().numpy()
+    assert_close(got if rows is None else got[:, :, rows], want, f"short heads {B},{H},{N},{d} {dtype} causal={causal} {order}")
+    from oracle import schedule_oracle as so
+    sched = so.schedule(B, H, N, causal, order, **oracle_inputs(info, d))
+    trace, count = trace.cpu(), count.cpu()
+    assert trace.shape[0] == len(sched)
+    for wg in range(info["grid"]):
+        assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == sched[wg], f"workgroup {wg}"
+    # the plain entry point runs the same thing
+    O2 = sa.attn_fwd(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order, o_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)

@@ -209,26 +209,35 @@ def test_schedule_oracle_hand_example_wide_tiles():
 # 256-row tiles (128 KiB LDS, 512 registers).  256-row tiles where the measured break-even says so: d = 128,
 # at least 32 such tiles of a head per XCD (64 under the causal mask).
 KERNEL_CHOICE = [
-    ((1, 1, 256, 64, False, "f16"), (64, 1, 8)),            # workload 1: four 64-row tiles, one head over 8 XCDs
-    ((1, 8, 2048, 64, False, "f16"), (64, 32, 256)),        # workload 2: 32 tiles of 64 rows per head, one head per XCD
-    ((1, 8, 2048, 64, True, "f16"), (128, 16, 128)),        # ... the halved scan is for unmasked binary16 problems only
-    ((1, 8, 2048, 64, False, "bf16"), (128, 16, 128)),
-    ((1, 8, 2048 + 64, 64, False, "f16"), (128, 17, 136)),  # ... with an even number of full K/V tiles
-    ((1, 16, 1024, 128, False, "f16"), (64, 16, 128)),      # 128 tiles of 128 rows: still at most half the CUs (two
-                                                            # heads per XCD, one after the other, 16 tiles of 64 rows each)
-    ((1, 17, 1024, 128, False, "f16"), (128, 1, 8)),        # 136 tiles: no longer (17 heads: 8 parts of one tile per head)
-    ((1, 16, 8192, 128, True, "bf16"), (128, 64, 512)),     # workload 3
-    ((1, 32, 16384, 128, False, "f16"), (256, 32, 256)),    # workload 4: 64 tiles of 256 rows per head
-    ((4, 32, 32768, 128, True, "bf16"), (256, 32, 256)),    # workload 5: 128 tiles of 256 rows per head
-    ((1, 8, 256 * 31, 128, False, "f16"), (128, 62, 496)),  # one tile short of the break-even
-    ((1, 8, 256 * 32, 128, False, "f16"), (256, 32, 256)),
-    ((1, 8, 256 * 63, 128, True, "f16"), (128, 64, 512)),   # under the mask the break-even is twice as far out
-    ((1, 8, 256 * 64, 128, True, "f16"), (256, 32, 256)),
-    ((1, 8, 256 * 70, 64, False, "f16"), (128, 96, 768)),   # d = 64: three workgroups per CU
-    ((1, 8, 256 * 70, 128, False, "bf16"), (256, 32, 256)),  # the element type plays no part
-    ((1, 1, 256 * 8 * 32, 128, False, "f16"), (256, 32, 256)),   # one head over 8 XCDs: 32 tiles each
-    ((1, 1, 256 * 8 * 31, 128, False, "f16"), (128, 62, 496)),
-    ((2, 3, 333, 128, False, "f16"), (128, 1, 8)),          # 6 heads: 4 parts per head, 3 tiles -> one per part
+    ((1, 1, 256, 64, False, "f16"), (64, 1, 8, "persistent")),            # workload 1: four 64-row tiles, one head over 8 XCDs
+    ((1, 8, 2048, 64, False, "f16"), (64, 32, 256, "persistent")),        # workload 2: 32 tiles of 64 rows per head, one head per XCD
+    ((1, 8, 2048, 64, True, "f16"), (128, 16, 128, "persistent")),        # ... the halved scan is for unmasked binary16 problems only
+    ((1, 8, 2048, 64, False, "bf16"), (128, 16, 128, "persistent")),
+    ((1, 8, 2048 + 64, 64, False, "f16"), (128, 17, 136, "persistent")),  # ... with an even number of full K/V tiles
+    ((1, 16, 1024, 128, False, "f16"), (64, 32, 256, "grid")),  # 128 tiles of 128 rows: still at most half the CUs; two
+                                                            # heads of 16 tiles (64 rows) per XCD: side by side
+    ((1, 17, 1024, 128, False, "f16"), (128, 17, 136, "grid")),     # 136 tiles: no longer halved; 17 heads in 8 parts of
+                                                                    # one tile each: 17 one-tile chunks per XCD, side by side
+    ((1, 16, 8192, 128, True, "bf16"), (128, 64, 512, "persistent")),     # workload 3
+    ((1, 32, 16384, 128, False, "f16"), (256, 32, 256, "persistent")),    # workload 4: 64 tiles of 256 rows per head
+    ((4, 32, 32768, 128, True, "bf16"), (256, 32, 256, "persistent")),    # workload 5: 128 tiles of 256 rows per head
+    ((1, 8, 256 * 31, 128, False, "f16"), (128, 62, 496, "persistent")),  # one tile short of the break-even
+    ((1, 8, 256 * 32, 128, False, "f16"), (256, 32, 256, "persistent")),
+    ((1, 8, 256 * 63, 128, True, "f16"), (128, 64, 512, "persistent")),   # under the mask the break-even is twice as far out
+    ((1, 8, 256 * 64, 128, True, "f16"), (256, 32, 256, "persistent")),
+    ((1, 8, 256 * 70, 64, False, "f16"), (128, 96, 768, "persistent")),   # d = 64: three workgroups per CU
+    ((1, 8, 256 * 70, 128, False, "bf16"), (256, 32, 256, "persistent")),  # the element type plays no part
+    ((1, 1, 256 * 8 * 32, 128, False, "f16"), (256, 32, 256, "persistent")),   # one head over 8 XCDs: 32 tiles each
+    ((1, 1, 256 * 8 * 31, 128, False, "f16"), (128, 62, 496, "persistent")),
+    ((2, 3, 333, 128, False, "f16"), (128, 3, 24, "grid")),         # 6 heads: 4 parts per head, 3 tiles -> at most one per
+                                                                    # part; 3 chunks per XCD, side by side
+    # short heads, several per XCD: the direct launch, one tile per workgroup, all heads of an XCD side by side
+    ((1, 128, 512, 64, False, "f16"), (128, 64, 512, "grid")),      # 16 heads of 4 tiles per XCD
+    ((1, 64, 2048, 64, True, "f16"), (128, 128, 1024, "grid")),     # 8 heads of 16 tiles per XCD, causal
+    ((1, 16, 4096, 64, False, "f16"), (128, 64, 512, "grid")),      # 2 heads of 32 tiles per XCD, no mask
+    ((1, 16, 4096, 64, True, "f16"), (128, 32, 256, "persistent")),  # ... causal: a long and a short tile per workgroup
+    ((1, 32, 4096, 128, True, "bf16"), (128, 128, 1024, "grid")),   # 4 causal heads of 32 tiles per XCD
+    ((1, 32, 8192, 128, True, "bf16"), (128, 64, 512, "persistent")),  # a head fills its XCD (64 tiles for 64 workgroups)
 ]
 
 
@@ -236,7 +245,8 @@ KERNEL_CHOICE = [
 def test_kernel_choice_by_hand_listed_cases(sa, shape, want):
     B, H, N, d, causal, dtype = shape
     info = sa.attn_fwd_launch_info(B, H, N, d, causal, dtype=dtype)
-    assert (info["tile_q"], info["slots"], info["grid"]) == want
+    assert (info["tile_q"], info["slots"], info["grid"], ["persistent", "grid"][info["launch"]]) == want
+    assert info["tiles_per_workgroup"] == 1      # (two only when a variant asks for the grid launch without saying)
     assert info == sa.attn_fwd_launch_info(B, H, N, d, causal, "cyclic", dtype)     # the order plays no part
     assert info == sa.attn_fwd_variant_launch_info(B, H, N, d, causal, None, dtype)
     assert info["tile_kv"] == 64 and info["block_threads"] == 256 and info["domains"] == 8
@@ -306,6 +316,19 @@ def test_host_plan_with_halved_scan_matches_schedule_oracle(sa, B, H, N, d, kw):
             assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == want[wg], f"workgroup {wg} {order}"
 
 
+def test_launch_left_open_in_a_variant_is_what_attn_fwd_runs(sa):
+    """launch = "auto" in a variant gives the launch attn_fwd picks; with slots_per_domain or the linear decode
+    given, that is the persistent one."""
+    for shape in ((1, 128, 512, 64, False), (1, 64, 2048, 64, True), (1, 16, 4096, 64, True), (1, 32, 16384, 128, False)):
+        assert sa.attn_fwd_variant_launch_info(*shape, sa.variant(launch="auto")) == sa.attn_fwd_launch_info(*shape)
+    assert sa.attn_fwd_launch_info(1, 128, 512, 64, False)["launch"] == sa.LAUNCH_GRID
+    assert sa.attn_fwd_variant_launch_info(1, 128, 512, 64, False, sa.variant(launch="auto", slots_per_domain=5))["launch"] \
+        == sa.LAUNCH_PERSISTENT
+    assert sa.attn_fwd_variant_launch_info(1, 128, 512, 64, False, sa.variant(launch="auto", decode="linear"))["launch"] \
+        == sa.LAUNCH_PERSISTENT
+    assert sa.attn_fwd_variant_launch_info(1, 128, 512, 64, False, sa.variant())["launch"] == sa.LAUNCH_PERSISTENT
+
+
 def test_halved_scan_is_refused_where_it_does_not_apply(sa):
     for args, kw in (((1, 8, 2048, 64, True), dict(kv_halves=2)),                       # causal mask
                      ((1, 8, 2048 + 64, 64, False), dict(kv_halves=2)),                 # odd number of K/V tiles
@@ -349,7 +372,7 @@ def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, 
 
 def test_variant_fields_are_validated(sa):
     vli = sa.attn_fwd_variant_launch_info
-    for bad in (dict(launch=2), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
+    for bad in (dict(launch=3), dict(launch=-1), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
                 dict(tiles_per_workgroup=3), dict(align_rounds=2), dict(align_rounds=-1)):
         with pytest.raises(binding.SawattnError) as e:
             vli(1, 8, 2048, 128, False, sa.variant(**bad))

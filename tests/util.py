@@ -33,10 +33,15 @@ RESIDENT_PER_XCD = {(64, 128): 96, (128, 128): 64, (128, 256): 32, (64, 64): 64,
 
 
 def oracle_inputs(info, d, variant_kw=None):
-    """Inputs of oracle.schedule_oracle for a launch of the library: the tile height the library reports (its choice
-    is pinned case by case in test_host_logic.py), the hand-listed resident count, and the variant's hand-out."""
+    """Inputs of oracle.schedule_oracle for a launch of the library: the tile height and the kind of launch the
+    library reports (its choices are pinned case by case in test_host_logic.py), the hand-listed resident count, and
+    the variant's work decode."""
     kw = dict(variant_kw or {})
     out = {k: v for k, v in kw.items() if k in ("launch", "decode", "tiles_per_workgroup")}
+    if kw.get("launch", "auto") == "auto":      # left open: what the library reports (persistent if it says nothing)
+        out["launch"] = ("persistent", "grid")[info.get("launch", 0)]
+    if out["launch"] == "grid" and "tiles_per_workgroup" not in out and "tiles_per_workgroup" in info:
+        out["tiles_per_workgroup"] = info["tiles_per_workgroup"]
     out["tile_q"] = info["tile_q"]
     out["resident"] = kw.get("slots_per_domain") or RESIDENT_PER_XCD[(d, info["tile_q"])]
     return out
