@@ -97,10 +97,12 @@ enum {
     SAWATTN_LAUNCH_GRID = 1,       /* Alg. 3: one workgroup per `tiles_per_workgroup` consecutive query
                                       tiles, handed to the hardware dispatcher */
     SAWATTN_LAUNCH_AUTO = 2        /* what attn_fwd does: PERSISTENT, except where a head has fewer query tiles than
-                                      an XCD holds workgroups and an XCD has three or more heads (two without the
-                                      causal mask) to go through -- then GRID with one tile per workgroup, so that
-                                      the tiles of several heads run side by side (with slots_per_domain or the
-                                      linear decode given: PERSISTENT) */
+                                      an XCD holds workgroups and an XCD has two or more heads to go through --
+                                      then GRID with one tile per workgroup, so that the tiles of several heads run
+                                      side by side (under the causal mask only for heads of at most half that many
+                                      tiles, and with two heads per XCD only if all their tiles fit the XCD's 32
+                                      compute units at once; with slots_per_domain or the linear decode given:
+                                      PERSISTENT) */
 };
 enum {
     SAWATTN_DECODE_DOMAIN = 0,     /* work is dealt out per XCD (one L2 each): the workgroups of an XCD

@@ -87,16 +87,20 @@ enum { kLaunchPersistent = 0, kLaunchGrid = 1 };
 // XCD holds workgroups then leaves compute units idle, and with several such heads per XCD one after the other
 // the launch takes several times longer than it has to (B*H = 128, N = 512, d = 64: 140 us against 17 us).  There
 // the direct launch of Alg. 3 with one tile per workgroup is taken: the hardware dispatcher runs the tiles of all
-// heads of an XCD side by side, still head by head in workgroup order.  Not for one or two causal heads per XCD,
-// where the persistent hand-out pairs a long tile with a short one per workgroup and the dispatcher cannot.
+// heads of an XCD side by side, still head by head in workgroup order.  Under the causal mask the persistent
+// hand-out has something the dispatcher has not -- it pairs a long tile with a short one per workgroup -- and keeps
+// the launch unless the heads are short enough to run two abreast (measured: from half the resident count down),
+// or, with only two heads per XCD, unless all their tiles find a compute unit of their own.
 SAW_HD int default_launch(int heads, int N, int d, bool causal, int tile_q) {
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int q_tiles = (N + tile_q - 1) / tile_q;
     const int per_part = (q_tiles + parts - 1) / parts;
     const long long chunks = ((long long)heads * parts) / kDomains;
     const int resident = tile_q > kTileQ ? 32 : (tile_q < kTileQ ? (d == 64 ? 64 : 32) : (d == 64 ? 96 : 64));
-    if (per_part >= resident) return kLaunchPersistent;
-    return chunks >= 3 || (!causal && chunks >= 2) ? kLaunchGrid : kLaunchPersistent;
+    if (per_part >= resident || chunks < 2) return kLaunchPersistent;
+    if (!causal) return kLaunchGrid;
+    if (chunks >= 3) return 2 * per_part <= resident ? kLaunchGrid : kLaunchPersistent;
+    return 2 * per_part <= 32 ? kLaunchGrid : kLaunchPersistent;
 }
 enum { kDecodeDomain = 0, kDecodeLinear = 1 };
 

@@ -236,6 +236,8 @@ KERNEL_CHOICE = [
     ((1, 64, 2048, 64, True, "f16"), (128, 128, 1024, "grid")),     # 8 heads of 16 tiles per XCD, causal
     ((1, 16, 4096, 64, False, "f16"), (128, 64, 512, "grid")),      # 2 heads of 32 tiles per XCD, no mask
     ((1, 16, 4096, 64, True, "f16"), (128, 32, 256, "persistent")),  # ... causal: a long and a short tile per workgroup
+    ((1, 16, 2048, 64, True, "f16"), (128, 32, 256, "grid")),       # ... unless both heads' tiles (2 x 16) fit the 32 CUs
+    ((1, 32, 8192, 64, True, "f16"), (128, 64, 512, "persistent")),  # 4 causal heads of 64 tiles: more than half of 96
     ((1, 32, 4096, 128, True, "bf16"), (128, 128, 1024, "grid")),   # 4 causal heads of 32 tiles per XCD
     ((1, 32, 8192, 128, True, "bf16"), (128, 64, 512, "persistent")),  # a head fills its XCD (64 tiles for 64 workgroups)
 ]
