@@ -17,6 +17,11 @@ Studies
   launch    Alg. 3 (direct launch, one or two query tiles per workgroup) against the persistent
             launch, both scan orders (Sec. 4.3's two program variants).
   batch     Sec. 4.2 / 4.3 shapes: d = 64, N = 128K (and 32K), B in {1, 2, 4, 8}, plain and causal.
+  heads     Alg. 2 against Alg. 3 where heads are short and come several to an XCD (B*H = 16...128, N = 512...8K):
+            the persistent launch, the direct launch with one tile per workgroup, and what attn_fwd picks by itself.
+
+A point without a variant runs what attn_fwd runs (launch left open); a variant pins the persistent launch unless
+it names the other.
 
 Inputs are seeded N(0,1) values rounded to fp16 (`workloads.make_random`), scale 1/sqrt(d).
 """
@@ -71,6 +76,14 @@ def study_points(study: str):
                 for B in (1, 2, 4, 8):
                     for order in ("cyclic", "sawtooth"):
                         pts.append(_pt(B, 1, N, 64, causal, order))
+    elif study == "heads":
+        for d in (64, 128):
+            for (H, N) in ((128, 512), (64, 1024), (64, 2048), (16, 2048), (24, 2048), (16, 4096), (32, 4096), (32, 8192)):
+                for causal in (False, True):
+                    # (what attn_fwd picks comes last: the first point of a shape meets a cold clock)
+                    for var in ({"launch": "persistent", "kv_halves": 1},
+                                {"launch": "grid", "tiles_per_workgroup": 1, "kv_halves": 1}, {}):
+                        pts.append(_pt(1, H, N, d, causal, "sawtooth", **var))
     else:
         raise SystemExit(f"unknown study {study!r}")
     return pts
@@ -96,7 +109,7 @@ def model(pt, info):
 
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
-    ap.add_argument("--study", required=True, choices=["seqlen", "resident", "decode", "launch", "batch"])
+    ap.add_argument("--study", required=True, choices=["seqlen", "resident", "decode", "launch", "batch", "heads"])
     ap.add_argument("--points", default="", help="comma-separated point indices or a:b ranges (default: all)")
     ap.add_argument("--launches", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
@@ -135,7 +148,7 @@ def main(argv=None):
             Q, K, V = workloads.make_random(*key, "f16", seed=1234 + pt["N"] % 977, device="cuda")
             cache[key] = (Q, K, V, torch.empty_like(Q))
         Q, K, V, O = cache[key]
-        var = sa.variant(**pt["variant"])
+        var = sa.variant(**pt["variant"]) if pt["variant"] else None      # None: what attn_fwd runs
         info = sa.attn_fwd_variant_launch_info(*key, pt["causal"], var, "f16")
         scale = 1.0 / math.sqrt(pt["d"])
 
@@ -154,7 +167,7 @@ def main(argv=None):
         flops = 4.0 * pt["B"] * pt["H"] * pt["N"] ** 2 * pt["d"] * (0.5 if pt["causal"] else 1.0)
         n = args.warmup + args.launches
         print(json.dumps({"study": args.study, "point": i, **pt, "grid": info["grid"], "slots": info["slots"],
-                          "tile_q": info["tile_q"],
+                          "tile_q": info["tile_q"], "launch": ("persistent", "grid")[info["launch"]],
                           "parts_per_head": info["parts_per_head"], "ms_median": ms[len(ms) // 2], "ms_min": ms[0],
                           "tflops": flops / (ms[len(ms) // 2] * 1e-3) / 1e12, "model": model(pt, info),
                           "dispatches": [dispatch, dispatch + n]}), flush=True)
