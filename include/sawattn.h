@@ -24,7 +24,7 @@ extern "C" {
 enum {
     SAWATTN_OK = 0,
     SAWATTN_ERR_INVALID_ARG = 1,   /* null / misaligned pointer, non-positive size, bad enum, overflow */
-    SAWATTN_ERR_UNSUPPORTED = 2,   /* head dimension other than 64 or 128 */
+    SAWATTN_ERR_UNSUPPORTED = 2,   /* head dimension other than 64 or 128; a variant the problem does not admit */
     SAWATTN_ERR_RUNTIME = 3        /* the HIP runtime refused the launch */
 };
 
@@ -50,7 +50,9 @@ enum {
 
 /*
  * attn_fwd -- O = softmax(Q K^T * scale) V  (paper Sec. 2.2, Eq. 1), computed tile by tile with an
- * online softmax (Alg. 1) by persistent workgroups (Alg. 2) that scan K/V in `scan_order` (Alg. 4).
+ * online softmax (Alg. 1) by persistent workgroups (Alg. 2) that scan K/V in `scan_order` (Alg. 4); where
+ * heads are short and come several to an XCD, by one workgroup per query tile instead (Alg. 3; see
+ * SAWATTN_LAUNCH_AUTO below).
  *
  *   Q, K, V  device, read only.  Contiguous [B, H, N, d], d fastest, element type `in_dtype`
  *            (SAWATTN_F16 or SAWATTN_BF16), 16-byte aligned.  Query and key sequences both have
