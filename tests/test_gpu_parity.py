@@ -628,3 +628,34 @@ def test_short_heads_run_side_by_side(sa, oracle, B, H, N, d, dtype, causal, ord
     O2 = sa.attn_fwd(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order, o_dtype=torch.float32)
     torch.cuda.synchronize()
     assert torch.equal(O, O2)
+
+
+# ------------------------------------------------------------------ whatever attn_fwd picks: random shapes
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_through_the_plain_entry_point(sa, oracle, seed):
+    """Shapes drawn at random around the points where attn_fwd changes what it runs (tile height, launch, halved scan):
+    every element against the oracle, both scan orders, and the launch info must describe a launch that covers all
+    query tiles."""
+    rng = np.random.default_rng(seed)
+    kinds = set()
+    for case in range(14):
+        d = int(rng.choice([64, 128]))
+        dtype = str(rng.choice(["f16", "bf16"]))
+        causal = bool(rng.integers(0, 2))
+        heads = int(rng.choice([1, 2, 3, 6, 8, 9, 16, 24, 40]))
+        N = int(rng.choice([64, 128, 200, 256, 384, 500, 512, 640, 1000, 1024, 1536, 2048]))
+        if heads * N > 24 * 1024:
+            N = max(64, (24 * 1024 // heads) // 64 * 64)
+        B = 2 if heads % 2 == 0 and rng.integers(0, 2) else 1
+        H = heads // B
+        info = sa.attn_fwd_launch_info(B, H, N, d, causal, "sawtooth", dtype)
+        kinds.add((info["tile_q"], info["launch"]))
+        assert info["grid"] == info["slots"] * 8
+        assert info["grid"] * info["max_local_tiles"] >= B * H * info["q_tiles_per_head"]
+        Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=1000 * seed + case)
+        scale = float(rng.choice([1.0, 0.5, 2.0])) / math.sqrt(d)
+        want = oracle.attention(Q, K, V, scale, causal=causal)
+        for order in ORDERS:
+            got = run_gpu(sa, Q, K, V, scale, causal, order, o_dtype=torch.float32)
+            assert_close(got, want, f"random case {seed}/{case}: {B},{H},{N},{d} {dtype} causal={causal} {order} {info}")
+    assert len(kinds) >= 3, kinds      # the draw reached several kinds of launch
