@@ -134,12 +134,13 @@ typedef struct sawattn_variant {
                                 every round as well, which holds them in the lockstep Sec. 3.4 assumes at a cost in
                                 time.  For measuring what the scan order can save at best.  Ignored otherwise. */
     int kv_halves;           /* 1: a workgroup's wavefronts each own query rows and walk the whole scan;
-                                2 (binary16 inputs, no causal mask, N a multiple of 128, 32 rows per wavefront;
-                                UNSUPPORTED otherwise): a workgroup takes 64 query rows, two wavefronts walk the
-                                first half of the K/V scan and two the second half, at once, and the two partial
-                                softmax results are merged before the output is written (Alg. 1's update applied
-                                to two partial results instead of one tile at a time) -- for problems too small to
-                                occupy the chip, where the length of one wavefront's walk is the launch time;
+                                2 (binary16 inputs, 32 rows per wavefront; UNSUPPORTED otherwise): a workgroup
+                                takes 64 query rows, two wavefronts walk the first half of the full, unmasked
+                                K/V tiles of the scan and two the second half, at once, and the two partial
+                                softmax results are merged (Alg. 1's update applied to two partial results
+                                instead of one tile at a time); an odd tile and the masked ones are taken by the
+                                first two wavefronts alone -- for problems too small to occupy the chip, where
+                                the length of one wavefront's walk is the launch time;
                                 0 = default: 2 where it is supported and B*H*ceil(N/128) <= 128, else 1. */
 } sawattn_variant;
 /*

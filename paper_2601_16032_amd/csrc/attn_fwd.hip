@@ -476,7 +476,9 @@ __device__ __forceinline__ void compute_tile(TileState<D>& st, const ReadAddr<D>
 template <int D, bool BF16, bool CAUSAL, bool MASKED, int NH>
 __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const LaneMap<D>& lm, const char* Kh, const char* Vh, int N,
                                               float c, int j_first, int step, int count, int qw0, int qrow, int lane,
-                                              LDS_PTR(char) lds) {
+                                              LDS_PTR(char) lds, bool idle = false) {
+    // idle: this wavefront fetches and keeps the barriers like the others but computes nothing (its rows are another
+    // wavefront's in this run)
     using G = Geo<D>;
     if (count <= 0) return;
     const unsigned lds0 = (unsigned)(size_t)lds;
@@ -515,7 +517,7 @@ __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const Lane
         const int kv0 = j * kTileKV;
 #pragma unroll
         for (int h = 0; h < NH; ++h) {   // half h: query rows qw0 + 32h .. +31 (this lane: qrow + 32h)
-            const bool active = qw0 + 32 * h < N && (!CAUSAL || kv0 <= qw0 + 32 * h + 31);
+            const bool active = !idle && qw0 + 32 * h < N && (!CAUSAL || kv0 <= qw0 + 32 * h + 31);
             if (active) compute_tile<D, BF16, CAUSAL, MASKED, NH == 2>(st[h], ra, c, kv0, qrow + 32 * h, lane, N);
         }
         ra.flip(cur ? -G::kTile : G::kTile);
@@ -1209,14 +1211,16 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 
 // One query tile (Alg. 1 body): rows [t*128*NH, (t+1)*128*NH) of head `hh`, K/V tiles j0, j0+step, ... (nkv of
 // them).  A wavefront owns NH halves of 32 query rows each (NH = 2: the wide variant).
-// HALVES (32 rows per wavefront, no mask, binary16 inputs, an even number of full K/V tiles): the tile has 64 rows,
-// wavefronts 0 and 1 take them over the first half of the scan, wavefronts 2 and 3 the same rows over the second
-// half, and the two partial results are merged through LDS before the epilogue (the merge of two softmax partials:
-// common reference maximum, both rescaled to it).
+// HALVES (32 rows per wavefront, binary16 inputs): the tile has 64 rows; of its full, unmasked K/V tiles wavefronts
+// 0 and 1 take the first half and wavefronts 2 and 3, for the same rows, the second half, at once, and the two partial
+// results are merged through LDS (the merge of two softmax partials: common reference maximum, both rescaled to it).
+// What does not split evenly or needs the mask -- an odd plain tile, the diagonal tile, a ragged last tile -- is taken
+// one tile at a time by wavefronts 0 and 1 alone, after the merge in a forward scan and before the halves in a
+// backward one, where it comes first.
 template <int D, bool BF16, bool CAUSAL, int NH, bool HALVES = false>
 __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>& lm, int hh, int t, int j0, int step,
                                                int nkv, int wave, int lane, LDS_PTR(char) lds) {
-    static_assert(!HALVES || (NH == 1 && !CAUSAL && !BF16), "two key ranges at once: 32-row kernel, no mask, binary16");
+    static_assert(!HALVES || (NH == 1 && !BF16), "two key ranges at once: 32-row kernel, binary16 inputs");
     using G = Geo<D>;
     constexpr int KS = D / 16;    // MFMA steps along d for S^T
     constexpr int DB = D / 32;    // 32-row blocks of O^T
@@ -1290,7 +1294,11 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         }
     };
     if constexpr (HALVES) {
-        pipelined_range<D, BF16, true>(st[0], lm, Kh, Vh, c, j0, step, nkv / 2, lane, lds, run);
+        const int half = n_plain / 2;                       // plain tiles per run
+        const int n_left = (n_plain & 1) + n_masked;        // tiles left for the tile-at-a-time code
+        if (step < 0)
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j0, step, n_left, qw0, qrow, lane, lds, run == 1);
+        pipelined_range<D, BF16, true>(st[0], lm, Kh, Vh, c, step > 0 ? j0 : j0 + n_left * step, step, half, lane, lds, run);
         // ---- merge: wavefront w + 2 hands (O^T, M, L) of its half to wavefront w, lane to lane, through LDS
         //      (value k of lane l of wavefront w + 2 at float index (2k + w) * 64 + l: no bank conflicts)
         constexpr int NV = DB * 16 + 2;
@@ -1317,7 +1325,10 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
             st[0].M = M;
             st[0].L = st[0].L * a0 + L1 * a1;
         }
-        __syncthreads();   // the exchange area is read before the next query tile's fetches overwrite it
+        __syncthreads();   // the exchange area is read before the next fetches overwrite it
+        if (step > 0)
+            general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j0 + 2 * half * step, step, n_left, qw0, qrow, lane,
+                                                     lds, run == 1);
         if (run == 1) return;
     } else if (step > 0) {
         plain(j0);
@@ -1474,14 +1485,20 @@ template <int D, bool BF16, bool CAUSAL, int NH, bool HALVES = false>
 int launch(Params& p, int grid, hipStream_t stream) {
     auto kern = attn_fwd_kernel<D, BF16, CAUSAL, NH, HALVES>;
     constexpr int lds_bytes = NH == 2 ? kWideLdsBytes : (HALVES ? 2 : 1) * Geo<D>::kLdsBytes;
-    static thread_local bool configured = false;
-    if (!configured) {
+    // The LDS size a kernel may ask for is a per-device attribute of the function: set once per device (bit = device).
+    static std::atomic<unsigned long long> configured{0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        (void)hipGetLastError();
+        return fail(SAWATTN_ERR_RUNTIME, "hipGetDevice failed (or more than 64 devices)");
+    }
+    if (!(configured.load(std::memory_order_acquire) >> dev & 1ull)) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 lds_bytes) != hipSuccess) {
             (void)hipGetLastError();
             return fail(SAWATTN_ERR_RUNTIME, "hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed");
         }
-        configured = true;
+        configured.fetch_or(1ull << dev, std::memory_order_release);
     }
     p.ticket_set = 0;
     if (p.sched.sync_heads || p.sched.sync_rounds) {
@@ -1507,9 +1524,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.kv_halves must be 0 (default), 1 or 2");
         halves = v->kv_halves;
         if (halves == 2) {
-            if (causal || bf16 || N % (2 * kTileKV) != 0)
-                return fail(SAWATTN_ERR_UNSUPPORTED,
-                            "variant.kv_halves = 2 needs binary16 inputs, no causal mask and N a multiple of 128");
+            if (bf16) return fail(SAWATTN_ERR_UNSUPPORTED, "variant.kv_halves = 2 needs binary16 inputs");
             if (v->rows_per_wavefront == 64)
                 return fail(SAWATTN_ERR_UNSUPPORTED, "variant.kv_halves = 2 goes with 32 rows per wavefront");
         }
@@ -1648,8 +1663,10 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         if (bf && !converted) return ca ? launch<128, true, true, 2>(p, grid, stream) : launch<128, true, false, 2>(p, grid, stream);
         return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
-    if (sched.tile_q < kTileQ)   // 64-row tiles: the two halves of the K/V scan at once (binary16, no mask)
-        return d == 128 ? launch<128, false, false, 1, true>(p, grid, stream) : launch<64, false, false, 1, true>(p, grid, stream);
+    if (sched.tile_q < kTileQ) {   // 64-row tiles: the two halves of the K/V scan at once (binary16 inputs)
+        if (d == 128) return ca ? launch<128, false, true, 1, true>(p, grid, stream) : launch<128, false, false, 1, true>(p, grid, stream);
+        return ca ? launch<64, false, true, 1, true>(p, grid, stream) : launch<64, false, false, 1, true>(p, grid, stream);
+    }
     if (d == 128) {
         if (bf) return ca ? launch<128, true, true, 1>(p, grid, stream) : launch<128, true, false, 1>(p, grid, stream);
         return ca ? launch<128, false, true, 1>(p, grid, stream) : launch<128, false, false, 1>(p, grid, stream);

@@ -66,10 +66,11 @@ SAW_HD int resident_slots(int d, int tile_q = kTileQ) {
 
 // Small problems: when the 128-row query tiles of the whole problem occupy at most half of the 256 compute units,
 // the launch takes as long as one wavefront needs to walk all K/V tiles of a head.  Then a workgroup takes 64 rows
-// instead and walks the two halves of the scan at once, two wavefronts each (no mask, binary16 inputs, an even
-// number of full K/V tiles).  1 = one scan per workgroup, 2 = two halves.
+// instead and walks the two halves of the scan at once, two wavefronts each (binary16 inputs).  1 = one scan per
+// workgroup, 2 = two halves.
 SAW_HD int default_kv_halves(int heads, int N, bool causal, bool bf16) {
-    if (causal || bf16 || N % (2 * kTileKV) != 0) return 1;
+    (void)causal;
+    if (bf16) return 1;
     const long long tiles = (long long)heads * ((N + kTileQ - 1) / kTileQ);
     return tiles <= 128 ? 2 : 1;
 }

@@ -535,33 +535,36 @@ def test_workspace_path_at_full_size(sa, oracle):
 
 # ------------------------------------------------------------------ the two halves of the K/V scan at once (small problems)
 @pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("B,H,N,d,kw", [
     (1, 1, 256, 64, {}), (1, 8, 2048, 64, {}), (2, 3, 384, 128, {}), (1, 5, 1280, 128, {}),
     (1, 8, 2048, 64, dict(slots_per_domain=3)),              # several rounds per head: both directions
     (1, 4, 1024, 128, dict(launch="grid")), (1, 6, 640, 64, dict(decode="linear", slots_per_domain=2)),
     (1, 16, 4096, 64, {}),                                    # not what attn_fwd would pick by itself: 512 tiles
+    (1, 3, 1, 64, {}), (1, 2, 63, 128, {}), (2, 2, 65, 64, {}), (1, 4, 200, 128, dict(slots_per_domain=1)),   # ragged
+    (1, 7, 1000, 64, {}), (1, 2, 1989, 128, dict(slots_per_domain=2)), (1, 3, 704, 64, dict(launch="grid")),
 ])
-def test_halved_scan_every_element(sa, oracle, B, H, N, d, kw, order):
+def test_halved_scan_every_element(sa, oracle, B, H, N, d, kw, order, causal):
     """kv_halves = 2: 64-row tiles, wavefronts 0-1 over the first half of the keys, 2-3 over the second, merged before
     the epilogue.  Every element against the oracle, the recorded schedule against the schedule oracle, and the
     single-scan kernel on the same inputs for comparison."""
     Q, K, V = workloads.make_random(B, H, N, d, "f16", seed=77 + N)
     scale = 1.0 / math.sqrt(d)
-    want = oracle.attention(Q, K, V, scale, causal=False)
+    want = oracle.attention(Q, K, V, scale, causal=causal)
     var = sa.variant(kv_halves=2, **kw)
-    info = sa.attn_fwd_variant_launch_info(B, H, N, d, False, var)
+    info = sa.attn_fwd_variant_launch_info(B, H, N, d, causal, var)
     assert info["tile_q"] == 64
-    O, trace, count = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=False, scan_order=order,
+    O, trace, count = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order,
                                           o_dtype=torch.float32, variant=var, trace=True)
     torch.cuda.synchronize()
-    assert_close(O.double().cpu().numpy(), want, f"halved scan {B},{H},{N},{d} {kw} {order}")
+    assert_close(O.double().cpu().numpy(), want, f"halved scan {B},{H},{N},{d} causal={causal} {kw} {order}")
     from oracle import schedule_oracle as so
-    sched = so.schedule(B, H, N, False, order, **oracle_inputs(info, d, kw))
+    sched = so.schedule(B, H, N, causal, order, **oracle_inputs(info, d, kw))
     trace, count = trace.cpu(), count.cpu()
     assert trace.shape[0] == len(sched)
     for wg in range(info["grid"]):
         assert [tuple(r) for r in trace[wg, : int(count[wg])].tolist()] == sched[wg], f"workgroup {wg}"
-    one = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=False, scan_order=order,
+    one = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order,
                               o_dtype=torch.float32, variant=sa.variant(kv_halves=1, **kw))
     torch.cuda.synchronize()
     assert_close(O.double().cpu().numpy(), one.double().cpu().numpy(), "halved against single scan")

@@ -211,9 +211,10 @@ def test_schedule_oracle_hand_example_wide_tiles():
 KERNEL_CHOICE = [
     ((1, 1, 256, 64, False, "f16"), (64, 1, 8, "persistent")),            # workload 1: four 64-row tiles, one head over 8 XCDs
     ((1, 8, 2048, 64, False, "f16"), (64, 32, 256, "persistent")),        # workload 2: 32 tiles of 64 rows per head, one head per XCD
-    ((1, 8, 2048, 64, True, "f16"), (128, 16, 128, "persistent")),        # ... the halved scan is for unmasked binary16 problems only
-    ((1, 8, 2048, 64, False, "bf16"), (128, 16, 128, "persistent")),
-    ((1, 8, 2048 + 64, 64, False, "f16"), (128, 17, 136, "persistent")),  # ... with an even number of full K/V tiles
+    ((1, 8, 2048, 64, True, "f16"), (64, 32, 256, "persistent")),         # ... also under the causal mask
+    ((1, 8, 2048, 64, False, "bf16"), (128, 16, 128, "persistent")),      # ... the halved scan is for binary16 inputs only
+    ((1, 8, 2000, 64, False, "f16"), (64, 32, 256, "persistent")),        # ... ragged lengths included (16 tiles of 128 rows)
+    ((1, 8, 2048 + 64, 64, False, "f16"), (128, 17, 136, "persistent")),  # 17 tiles of 128 rows per head: 136 in all, too many
     ((1, 16, 1024, 128, False, "f16"), (64, 32, 256, "grid")),  # 128 tiles of 128 rows: still at most half the CUs; two
                                                             # heads of 16 tiles (64 rows) per XCD: side by side
     ((1, 17, 1024, 128, False, "f16"), (128, 17, 136, "grid")),     # 136 tiles: no longer halved; 17 heads in 8 parts of
@@ -229,8 +230,10 @@ KERNEL_CHOICE = [
     ((1, 8, 256 * 70, 128, False, "bf16"), (256, 32, 256, "persistent")),  # the element type plays no part
     ((1, 1, 256 * 8 * 32, 128, False, "f16"), (256, 32, 256, "persistent")),   # one head over 8 XCDs: 32 tiles each
     ((1, 1, 256 * 8 * 31, 128, False, "f16"), (128, 62, 496, "persistent")),
-    ((2, 3, 333, 128, False, "f16"), (128, 3, 24, "grid")),         # 6 heads: 4 parts per head, 3 tiles -> at most one per
-                                                                    # part; 3 chunks per XCD, side by side
+    ((2, 3, 333, 128, False, "f16"), (64, 6, 48, "grid")),          # 6 heads of 6 tiles of 64 rows (18 of 128: a small
+                                                                    # problem), 4 parts per head of at most 2 tiles; 3
+                                                                    # chunks per XCD, side by side
+    ((2, 3, 333, 128, False, "bf16"), (128, 3, 24, "grid")),        # ... bfloat16: 128-row tiles, at most one per part
     # short heads, several per XCD: the direct launch, one tile per workgroup, all heads of an XCD side by side
     ((1, 128, 512, 64, False, "f16"), (128, 64, 512, "grid")),      # 16 heads of 4 tiles per XCD
     ((1, 64, 2048, 64, True, "f16"), (128, 128, 1024, "grid")),     # 8 heads of 16 tiles per XCD, causal
@@ -332,10 +335,7 @@ def test_launch_left_open_in_a_variant_is_what_attn_fwd_runs(sa):
 
 
 def test_halved_scan_is_refused_where_it_does_not_apply(sa):
-    for args, kw in (((1, 8, 2048, 64, True), dict(kv_halves=2)),                       # causal mask
-                     ((1, 8, 2048 + 64, 64, False), dict(kv_halves=2)),                 # odd number of K/V tiles
-                     ((1, 8, 2000, 64, False), dict(kv_halves=2)),                      # ragged last tile
-                     ((1, 8, 2048, 128, False), dict(kv_halves=2, rows_per_wavefront=64))):
+    for args, kw in (((1, 8, 2048, 128, False), dict(kv_halves=2, rows_per_wavefront=64)),):
         with pytest.raises(sa.SawattnError) as e:
             sa.attn_fwd_variant_launch_info(*args, sa.variant(**kw))
         assert e.value.code == sa.ERR_UNSUPPORTED
