@@ -1538,7 +1538,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
         if (v->rows_per_wavefront == 64 && d != 128)
             return fail(SAWATTN_ERR_UNSUPPORTED, "variant.rows_per_wavefront = 64 needs head dimension 128");
         rows = v->rows_per_wavefront;
-        if (halves == 0) halves = rows == 64 ? 1 : default_kv_halves(B * H, N, causal, bf16);
+        if (halves == 0) halves = rows == 64 ? 1 : default_kv_halves(B * H, N, d, causal, bf16);
         if (halves == 2) rows = 32;
         if (rows == 0) rows = v->slots_per_domain > resident_slots(d, 2 * kTileQ) ? 32 : default_rows_per_wavefront(B * H, N, d, causal, bf16);
         if (v->slots_per_domain < 0 ||
@@ -1556,7 +1556,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.align_rounds must be 0 or 1");
         align_rounds = v->align_rounds == 1;
     }
-    if (halves == 0) halves = default_kv_halves(B * H, N, causal, bf16);
+    if (halves == 0) halves = default_kv_halves(B * H, N, d, causal, bf16);
     if (halves == 2) rows = 32;
     if (rows == 0) rows = default_rows_per_wavefront(B * H, N, d, causal, bf16);
     const int tile_q = rows == 64 ? 2 * kTileQ : (halves == 2 ? kTileQ / 2 : kTileQ);
