@@ -134,7 +134,7 @@ typedef struct sawattn_variant {
                                 every round as well, which holds them in the lockstep Sec. 3.4 assumes at a cost in
                                 time.  For measuring what the scan order can save at best.  Ignored otherwise. */
     int kv_halves;           /* 1: a workgroup's wavefronts each own query rows and walk the whole scan;
-                                2 (binary16 inputs, 32 rows per wavefront; UNSUPPORTED otherwise): a workgroup
+                                2 (32 rows per wavefront; UNSUPPORTED with 64): a workgroup
                                 takes 64 query rows, two wavefronts walk the first half of the full, unmasked
                                 K/V tiles of the scan and two the second half, at once, and the two partial
                                 softmax results are merged (Alg. 1's update applied to two partial results

@@ -542,12 +542,12 @@ __device__ __forceinline__ void general_range(TileState<D> (&st)[NH], const Lane
 // HALVES: the workgroup walks two runs of `count` tiles at once -- run r = tiles j_first + (r*count + i)*step,
 // i = 0..count-1 -- for small problems, where the chip has more compute units than there are query tiles and
 // the length of one wavefront's walk is what the launch takes.  All four wavefronts fetch the tiles of both
-// runs (a second set of K/V buffers behind the first); this wavefront computes on run `run`.  binary16 inputs only.
+// runs (a second set of K/V buffers behind the first; for bfloat16 inputs a second set of V registers);
+// this wavefront computes on run `run`.
 template <int D, bool BF16, bool HALVES = false>
 __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<D>& lm, const char* Kh, const char* Vh,
                                                 float c, int j_first, int step, int count, int lane, LDS_PTR(char) lds,
                                                 int run = 0) {
-    static_assert(!(HALVES && BF16), "two runs at once: binary16 inputs only");
     using G = Geo<D>;
     constexpr int RUNS = HALVES ? 2 : 1;
     constexpr unsigned kSet = 4 * G::kTile;   // one set of buffers: K0 K1 V0 V1
@@ -564,7 +564,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
     f16v A[2];          // S^T of the tile one ahead: block b = keys 32b..32b+31 of the tile
     float x[32];        // score*c - M of the current tile, index 16*b + r
     u4 pf[4];           // its probabilities as B operands
-    u4 vreg[NL];        // bfloat16 V chunks in flight (BF16 only)
+    u4 vreg[(HALVES ? 2 : 1) * NL];   // bfloat16 V chunks in flight (BF16 only), run r in vreg[r * NL ...]
 
     // LDS read addresses: K of the tile one ahead, V of the current tile
     unsigned rk[KS], rv[DB][2];
@@ -626,10 +626,17 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
     // ---------------------------------------------------------------- prologue: tile 0
     fetch_burst(Kh, 0, lds0);
     if constexpr (BF16) {
-        const char* base = tile_base(Vh, 0);
 #pragma unroll
-        for (int l = 0; l < NL; ++l) vreg[l] = *reinterpret_cast<const u4*>(base + lm.fill_src[l]);
-        regs_to_lds_f16<D>(vreg, lm, lane, lds + 2 * G::kTile);
+        for (int r = 0; r < RUNS; ++r) {
+            const char* base = tile_base(Vh, 0, r);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) vreg[r * NL + l] = *reinterpret_cast<const u4*>(base + lm.fill_src[l]);
+        }
+#pragma unroll
+        for (int r = 0; r < RUNS; ++r)
+#pragma unroll
+            for (int l = 0; l < NL; ++l)
+                *(LDS_PTR(u4))(lds + r * kSet + 2 * G::kTile + lm.fill_dst + l * 4096 + lane * 16) = bf16x8_to_f16x8(vreg[r * NL + l]);
     } else {
         fetch_burst(Vh, 0, lds0 + 2 * G::kTile);
     }
@@ -695,7 +702,7 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
                     if (what < RUNS) {
                         if (FETCH_K) load_to_lds_16B(what ? kbase1 : kbase, lm.fill_src[l], kdst + what * kSet + l * 4096);
                     } else if constexpr (BF16) {
-                        vreg[l] = *reinterpret_cast<const u4*>(vbase + lm.fill_src[l]);
+                        vreg[(what - RUNS) * NL + l] = *reinterpret_cast<const u4*>((what - RUNS ? vbase1 : vbase) + lm.fill_src[l]);
                     } else {
                         load_to_lds_16B(what - RUNS ? vbase1 : vbase, lm.fill_src[l], vdst + (what - RUNS) * kSet + l * 4096);
                     }
@@ -736,7 +743,8 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
         //      bfloat16, the conversion of the fetched V chunks).  If the reference maximum has to
         //      be raised (need), the shifted scores are recomputed after the loop exit.
         constexpr int FPS = 32 / (NB - H);   // fmas per slot
-        constexpr int CPS = (NL * 4 + (NB - H) - 1) / (NB - H);   // bf16 pair conversions per slot
+        constexpr int CW = RUNS * NL * 4;                        // 32-bit words of bfloat16 V to convert
+        constexpr int CPS = (CW + (NB - H) - 1) / (NB - H);      // ... per slot
 #pragma unroll
         for (int idx = H; idx < NB; ++idx) {
             if (idx + 2 < NB) av[idx + 2] = v_read(idx + 2);
@@ -751,13 +759,13 @@ __device__ __forceinline__ void pipelined_range(TileState<D>& st, const LaneMap<
 #pragma unroll
                 for (int q = 0; q < CPS; ++q) {
                     const int w = (idx - H) * CPS + q;    // w-th 32-bit word of the fetched chunks
-                    if (w < NL * 4) {
+                    if (w < CW) {
                         f2 y;
                         y[0] = __builtin_bit_cast(float, vreg[w / 4][w % 4] << 16);
                         y[1] = __builtin_bit_cast(float, vreg[w / 4][w % 4] & 0xffff0000u);
                         vreg[w / 4][w % 4] = __builtin_bit_cast(unsigned, __builtin_convertvector(y, h2));
-                        if (w % 4 == 3)
-                            *(LDS_PTR(u4))(size_t)(vdst + (w / 4) * 4096 + lane * 16) = vreg[w / 4];
+                        if (w % 4 == 3)   // chunk w/4 = load (w/4) % NL of run (w/4) / NL
+                            *(LDS_PTR(u4))(size_t)(vdst + ((w / 4) / NL) * kSet + ((w / 4) % NL) * 4096 + lane * 16) = vreg[w / 4];
                     }
                 }
             }
@@ -1211,7 +1219,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 
 // One query tile (Alg. 1 body): rows [t*128*NH, (t+1)*128*NH) of head `hh`, K/V tiles j0, j0+step, ... (nkv of
 // them).  A wavefront owns NH halves of 32 query rows each (NH = 2: the wide variant).
-// HALVES (32 rows per wavefront, binary16 inputs): the tile has 64 rows; of its full, unmasked K/V tiles wavefronts
+// HALVES (32 rows per wavefront): the tile has 64 rows; of its full, unmasked K/V tiles wavefronts
 // 0 and 1 take the first half and wavefronts 2 and 3, for the same rows, the second half, at once, and the two partial
 // results are merged through LDS (the merge of two softmax partials: common reference maximum, both rescaled to it).
 // What does not split evenly or needs the mask -- an odd plain tile, the diagonal tile, a ragged last tile -- is taken
@@ -1220,7 +1228,7 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
 template <int D, bool BF16, bool CAUSAL, int NH, bool HALVES = false>
 __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>& lm, int hh, int t, int j0, int step,
                                                int nkv, int wave, int lane, LDS_PTR(char) lds) {
-    static_assert(!HALVES || (NH == 1 && !BF16), "two key ranges at once: 32-row kernel, binary16 inputs");
+    static_assert(!HALVES || NH == 1, "two key ranges at once: 32-row kernel");
     using G = Geo<D>;
     constexpr int KS = D / 16;    // MFMA steps along d for S^T
     constexpr int DB = D / 32;    // 32-row blocks of O^T
@@ -1524,7 +1532,6 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.kv_halves must be 0 (default), 1 or 2");
         halves = v->kv_halves;
         if (halves == 2) {
-            if (bf16) return fail(SAWATTN_ERR_UNSUPPORTED, "variant.kv_halves = 2 needs binary16 inputs");
             if (v->rows_per_wavefront == 64)
                 return fail(SAWATTN_ERR_UNSUPPORTED, "variant.kv_halves = 2 goes with 32 rows per wavefront");
         }
@@ -1663,8 +1670,12 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
         if (bf && !converted) return ca ? launch<128, true, true, 2>(p, grid, stream) : launch<128, true, false, 2>(p, grid, stream);
         return ca ? launch<128, false, true, 2>(p, grid, stream) : launch<128, false, false, 2>(p, grid, stream);
     }
-    if (sched.tile_q < kTileQ) {   // 64-row tiles: the two halves of the K/V scan at once (binary16 inputs)
-        if (d == 128) return ca ? launch<128, false, true, 1, true>(p, grid, stream) : launch<128, false, false, 1, true>(p, grid, stream);
+    if (sched.tile_q < kTileQ) {   // 64-row tiles: the two halves of the K/V scan at once
+        if (d == 128) {
+            if (bf) return ca ? launch<128, true, true, 1, true>(p, grid, stream) : launch<128, true, false, 1, true>(p, grid, stream);
+            return ca ? launch<128, false, true, 1, true>(p, grid, stream) : launch<128, false, false, 1, true>(p, grid, stream);
+        }
+        if (bf) return ca ? launch<64, true, true, 1, true>(p, grid, stream) : launch<64, true, false, 1, true>(p, grid, stream);
         return ca ? launch<64, false, true, 1, true>(p, grid, stream) : launch<64, false, false, 1, true>(p, grid, stream);
     }
     if (d == 128) {

@@ -66,12 +66,12 @@ SAW_HD int resident_slots(int d, int tile_q = kTileQ) {
 
 // Small problems: when the 128-row query tiles of the whole problem occupy at most half of the 256 compute units,
 // the launch takes as long as one wavefront needs to walk all K/V tiles of a head.  Then a workgroup takes 64 rows
-// instead and walks the two halves of the scan at once, two wavefronts each (binary16 inputs).  At d = 64, where two
+// instead and walks the two halves of the scan at once, two wavefronts each.  At d = 64, where two
 // such workgroups fit a compute unit, this still pays with one 128-row tile per compute unit (measured: 1.1-1.2x at
 // 256 tiles; at d = 128 a loss there).  1 = one scan per workgroup, 2 = two halves.
 SAW_HD int default_kv_halves(int heads, int N, int d, bool causal, bool bf16) {
     (void)causal;
-    if (bf16) return 1;
+    (void)bf16;
     const long long tiles = (long long)heads * ((N + kTileQ - 1) / kTileQ);
     return tiles <= (d == 64 ? 256 : 128) ? 2 : 1;
 }

@@ -545,19 +545,34 @@ def test_workspace_path_at_full_size(sa, oracle):
     (1, 7, 1000, 64, {}), (1, 2, 1989, 128, dict(slots_per_domain=2)), (1, 3, 704, 64, dict(launch="grid")),
 ])
 def test_halved_scan_every_element(sa, oracle, B, H, N, d, kw, order, causal):
+    _halved_scan_case(sa, oracle, B, H, N, d, kw, order, causal, "f16")
+
+
+@pytest.mark.parametrize("order", ORDERS)
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,N,d,kw", [
+    (1, 8, 2048, 64, {}), (2, 3, 384, 128, {}), (1, 8, 2048, 128, dict(slots_per_domain=3)), (1, 7, 1000, 64, {}),
+    (1, 2, 1989, 128, dict(slots_per_domain=2)), (1, 3, 704, 64, dict(launch="grid")), (1, 3, 1, 128, {}),
+])
+def test_halved_scan_every_element_bf16(sa, oracle, B, H, N, d, kw, order, causal):
+    """bfloat16 inputs: V of both runs goes through registers and is converted on its way into LDS."""
+    _halved_scan_case(sa, oracle, B, H, N, d, kw, order, causal, "bf16")
+
+
+def _halved_scan_case(sa, oracle, B, H, N, d, kw, order, causal, dtype):
     """kv_halves = 2: 64-row tiles, wavefronts 0-1 over the first half of the keys, 2-3 over the second, merged before
     the epilogue.  Every element against the oracle, the recorded schedule against the schedule oracle, and the
     single-scan kernel on the same inputs for comparison."""
-    Q, K, V = workloads.make_random(B, H, N, d, "f16", seed=77 + N)
+    Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=77 + N)
     scale = 1.0 / math.sqrt(d)
     want = oracle.attention(Q, K, V, scale, causal=causal)
     var = sa.variant(kv_halves=2, **kw)
-    info = sa.attn_fwd_variant_launch_info(B, H, N, d, causal, var)
+    info = sa.attn_fwd_variant_launch_info(B, H, N, d, causal, var, dtype)
     assert info["tile_q"] == 64
     O, trace, count = sa.attn_fwd_variant(Q.cuda(), K.cuda(), V.cuda(), scale=scale, causal=causal, scan_order=order,
                                           o_dtype=torch.float32, variant=var, trace=True)
     torch.cuda.synchronize()
-    assert_close(O.double().cpu().numpy(), want, f"halved scan {B},{H},{N},{d} causal={causal} {kw} {order}")
+    assert_close(O.double().cpu().numpy(), want, f"halved scan {B},{H},{N},{d} {dtype} causal={causal} {kw} {order}")
     from oracle import schedule_oracle as so
     sched = so.schedule(B, H, N, causal, order, **oracle_inputs(info, d, kw))
     trace, count = trace.cpu(), count.cpu()
@@ -645,10 +660,10 @@ def test_random_shapes_through_the_plain_entry_point(sa, oracle, seed):
         d = int(rng.choice([64, 128]))
         dtype = str(rng.choice(["f16", "bf16"]))
         causal = bool(rng.integers(0, 2))
-        heads = int(rng.choice([1, 2, 3, 6, 8, 9, 16, 24, 40]))
-        N = int(rng.choice([64, 128, 200, 256, 384, 500, 512, 640, 1000, 1024, 1536, 2048]))
-        if heads * N > 24 * 1024:
-            N = max(64, (24 * 1024 // heads) // 64 * 64)
+        heads = int(rng.choice([1, 2, 3, 6, 8, 9, 16, 24, 40, 64]))
+        N = int(rng.choice([64, 128, 200, 256, 384, 500, 512, 640, 1000, 1024, 1536, 2048, 3000, 4096]))
+        if heads * N > 64 * 1024:
+            N = max(64, (64 * 1024 // heads) // 64 * 64)
         B = 2 if heads % 2 == 0 and rng.integers(0, 2) else 1
         H = heads // B
         info = sa.attn_fwd_launch_info(B, H, N, d, causal, "sawtooth", dtype)

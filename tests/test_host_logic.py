@@ -212,7 +212,7 @@ KERNEL_CHOICE = [
     ((1, 1, 256, 64, False, "f16"), (64, 1, 8, "persistent")),            # workload 1: four 64-row tiles, one head over 8 XCDs
     ((1, 8, 2048, 64, False, "f16"), (64, 32, 256, "persistent")),        # workload 2: 32 tiles of 64 rows per head, one head per XCD
     ((1, 8, 2048, 64, True, "f16"), (64, 32, 256, "persistent")),         # ... also under the causal mask
-    ((1, 8, 2048, 64, False, "bf16"), (128, 16, 128, "persistent")),      # ... the halved scan is for binary16 inputs only
+    ((1, 8, 2048, 64, False, "bf16"), (64, 32, 256, "persistent")),       # ... and for bfloat16 inputs
     ((1, 8, 2000, 64, False, "f16"), (64, 32, 256, "persistent")),        # ... ragged lengths included (16 tiles of 128 rows)
     ((1, 8, 2048 + 64, 128, False, "f16"), (128, 17, 136, "persistent")),  # 17 tiles of 128 rows per head: 136 in all, too
                                                                             # many at d = 128
@@ -236,7 +236,7 @@ KERNEL_CHOICE = [
     ((2, 3, 333, 128, False, "f16"), (64, 6, 48, "grid")),          # 6 heads of 6 tiles of 64 rows (18 of 128: a small
                                                                     # problem), 4 parts per head of at most 2 tiles; 3
                                                                     # chunks per XCD, side by side
-    ((2, 3, 333, 128, False, "bf16"), (128, 3, 24, "grid")),        # ... bfloat16: 128-row tiles, at most one per part
+    ((2, 3, 333, 128, False, "bf16"), (64, 6, 48, "grid")),         # ... whatever the input type
     # short heads, several per XCD: the direct launch, one tile per workgroup, all heads of an XCD side by side
     ((1, 128, 512, 64, False, "f16"), (128, 64, 512, "grid")),      # 16 heads of 4 tiles per XCD
     ((1, 64, 2048, 64, True, "f16"), (128, 128, 1024, "grid")),     # 8 heads of 16 tiles per XCD, causal
@@ -344,9 +344,7 @@ def test_halved_scan_is_refused_where_it_does_not_apply(sa):
         with pytest.raises(sa.SawattnError) as e:
             sa.attn_fwd_variant_launch_info(*args, sa.variant(**kw))
         assert e.value.code == sa.ERR_UNSUPPORTED
-    with pytest.raises(sa.SawattnError) as e:
-        sa.attn_fwd_variant_launch_info(1, 8, 2048, 64, False, sa.variant(kv_halves=2), "bf16")
-    assert e.value.code == sa.ERR_UNSUPPORTED
+    assert sa.attn_fwd_variant_launch_info(1, 8, 2048, 64, False, sa.variant(kv_halves=2), "bf16")["tile_q"] == 64
     for bad in (-1, 3):
         with pytest.raises(sa.SawattnError) as e:
             sa.attn_fwd_variant_launch_info(1, 8, 2048, 64, False, sa.variant(kv_halves=bad))
