@@ -66,14 +66,17 @@ SAW_HD int resident_slots(int d, int tile_q = kTileQ) {
 
 // Small problems: when the 128-row query tiles of the whole problem occupy at most half of the 256 compute units,
 // the launch takes as long as one wavefront needs to walk all K/V tiles of a head.  Then a workgroup takes 64 rows
-// instead and walks the two halves of the scan at once, two wavefronts each.  At d = 64, where two
-// such workgroups fit a compute unit, this still pays with one 128-row tile per compute unit (measured: 1.1-1.2x at
-// 256 tiles; at d = 128 a loss there).  1 = one scan per workgroup, 2 = two halves.
+// instead and walks the two halves of the scan at once, two wavefronts each.  At d = 64, where two such workgroups
+// fit a compute unit (512 on the chip), it goes on paying for somewhat larger problems, most under the causal mask,
+// where the longest tile of a head sets the pace and is the one cut in two.  Measured limits, in 128-row tiles of the
+// whole problem: d = 128: 128 (beyond, the 64-row workgroups, one per compute unit, no longer run all at once: up to
+// 1.5x slower at 256); d = 64: 384 plain, 512 causal (gains of 3-10 % there, none at 768).
+// 1 = one scan per workgroup, 2 = two halves.
 SAW_HD int default_kv_halves(int heads, int N, int d, bool causal, bool bf16) {
-    (void)causal;
     (void)bf16;
     const long long tiles = (long long)heads * ((N + kTileQ - 1) / kTileQ);
-    return tiles <= (d == 64 ? 256 : 128) ? 2 : 1;
+    const int limit = d == 64 ? (causal ? 512 : 384) : 128;
+    return tiles <= limit ? 2 : 1;
 }
 
 // Besides that default, the launch variants the paper describes are kept selectable so that they

@@ -217,7 +217,10 @@ KERNEL_CHOICE = [
     ((1, 8, 2048 + 64, 128, False, "f16"), (128, 17, 136, "persistent")),  # 17 tiles of 128 rows per head: 136 in all, too
                                                                             # many at d = 128
     ((1, 8, 4096, 64, False, "f16"), (64, 64, 512, "persistent")),        # ... d = 64: up to 256 tiles of 128 rows
-    ((1, 8, 4096 + 64, 64, False, "f16"), (128, 33, 264, "persistent")),  # ... 264: too many
+    ((1, 8, 6144, 64, False, "f16"), (64, 64, 512, "persistent")),        # ... up to 384 (96 tiles of 64 rows per head)
+    ((1, 8, 6144 + 64, 64, False, "f16"), (128, 49, 392, "persistent")),  # ... 392: too many
+    ((1, 8, 8192, 64, True, "f16"), (64, 64, 512, "persistent")),         # ... under the causal mask up to 512
+    ((1, 8, 8192 + 64, 64, True, "f16"), (128, 65, 520, "persistent")),
     ((1, 16, 1024, 128, False, "f16"), (64, 32, 256, "grid")),  # 128 tiles of 128 rows: still at most half the CUs; two
                                                             # heads of 16 tiles (64 rows) per XCD: side by side
     ((1, 17, 1024, 128, False, "f16"), (128, 17, 136, "grid")),     # 136 tiles: no longer halved; 17 heads in 8 parts of
@@ -241,7 +244,7 @@ KERNEL_CHOICE = [
     ((1, 128, 512, 64, False, "f16"), (128, 64, 512, "grid")),      # 16 heads of 4 tiles per XCD
     ((1, 64, 2048, 64, True, "f16"), (128, 128, 1024, "grid")),     # 8 heads of 16 tiles per XCD, causal
     ((1, 16, 4096, 64, False, "f16"), (128, 64, 512, "grid")),      # 2 heads of 32 tiles per XCD, no mask
-    ((1, 16, 4096, 64, True, "f16"), (128, 32, 256, "persistent")),  # ... causal: a long and a short tile per workgroup
+    ((1, 16, 4096, 128, True, "f16"), (128, 32, 256, "persistent")),  # ... causal: a long and a short tile per workgroup
     ((1, 16, 2048, 128, True, "f16"), (128, 32, 256, "grid")),      # ... unless both heads' tiles (2 x 16) fit the 32 CUs
     ((1, 16, 2048, 64, True, "f16"), (64, 32, 256, "persistent")),  # (at d = 64 this is still a small problem: 64-row tiles,
                                                                     # 2 x 32 of them per XCD, a long and a short one each)
