@@ -142,7 +142,7 @@ typedef struct sawattn_variant {
                                 first two wavefronts alone -- for problems too small to occupy the chip, where
                                 the length of one wavefront's walk is the launch time;
                                 0 = default: 2 where it is supported and B*H*ceil(N/128) is at most 128 (d = 128),
-                                384 (d = 64) or 512 (d = 64 under the causal mask), else 1. */
+                                or, with d = 64 and N >= 2048, 384 (512 under the causal mask); else 1. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round

@@ -70,12 +70,13 @@ SAW_HD int resident_slots(int d, int tile_q = kTileQ) {
 // fit a compute unit (512 on the chip), it goes on paying for somewhat larger problems, most under the causal mask,
 // where the longest tile of a head sets the pace and is the one cut in two.  Measured limits, in 128-row tiles of the
 // whole problem: d = 128: 128 (beyond, the 64-row workgroups, one per compute unit, no longer run all at once: up to
-// 1.5x slower at 256); d = 64: 384 plain, 512 causal (gains of 3-10 % there, none at 768).
+// 1.5x slower at 256); d = 64: 384 plain, 512 causal (gains of 3-10 % there, none at 768), and beyond 128 only for
+// N >= 2048: a scan of 16 tiles or fewer is too short for its halves to pay for the merge (N = 512: 25 % slower).
 // 1 = one scan per workgroup, 2 = two halves.
 SAW_HD int default_kv_halves(int heads, int N, int d, bool causal, bool bf16) {
     (void)bf16;
     const long long tiles = (long long)heads * ((N + kTileQ - 1) / kTileQ);
-    const int limit = d == 64 ? (causal ? 512 : 384) : 128;
+    const int limit = d == 64 && N >= 2048 ? (causal ? 512 : 384) : 128;
     return tiles <= limit ? 2 : 1;
 }
 

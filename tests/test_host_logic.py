@@ -221,6 +221,7 @@ KERNEL_CHOICE = [
     ((1, 8, 6144 + 64, 64, False, "f16"), (128, 49, 392, "persistent")),  # ... 392: too many
     ((1, 8, 8192, 64, True, "f16"), (64, 64, 512, "persistent")),         # ... under the causal mask up to 512
     ((1, 8, 8192 + 64, 64, True, "f16"), (128, 65, 520, "persistent")),
+    ((1, 32, 1024, 64, False, "f16"), (128, 32, 256, "grid")),            # ... and only for N >= 2048: 256 tiles, short scans
     ((1, 16, 1024, 128, False, "f16"), (64, 32, 256, "grid")),  # 128 tiles of 128 rows: still at most half the CUs; two
                                                             # heads of 16 tiles (64 rows) per XCD: side by side
     ((1, 17, 1024, 128, False, "f16"), (128, 17, 136, "grid")),     # 136 tiles: no longer halved; 17 heads in 8 parts of
