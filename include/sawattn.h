@@ -127,8 +127,10 @@ typedef struct sawattn_variant {
                                 most 32 per XCD), every K/V fragment read from LDS feeds two MFMAs; same
                                 arithmetic as the 32-row kernel;
                                 0 = default: 64 for d = 128, slots_per_domain <= 32 and sequences long enough
-                                that every workgroup of an XCD gets at least one 256-row tile of a head (two
-                                under the causal mask): ceil(ceil(N/256) / parts_per_head) >= 32 (64); else 32. */
+                                that every workgroup of an XCD gets at least one 256-row tile of a head (nearly
+                                two under the causal mask) and the rounds of 32 tiles are well filled: with
+                                q = ceil(ceil(N/256) / parts_per_head), q >= 32 (56) and q at least 4/5 (3/4) of
+                                32 * ceil(q/32); else 32. */
     int align_rounds;        /* persistent launch with the per-XCD decode: 0 = the workgroups of an XCD wait for each
                                 other between heads only (and only where they finish a head together); 1 = after
                                 every round as well, which holds them in the lockstep Sec. 3.4 assumes at a cost in

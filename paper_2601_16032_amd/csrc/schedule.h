@@ -43,15 +43,22 @@ SAW_HD int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b);
 
 // Rows per wavefront when the caller leaves the choice open: the wide variant (64 rows, 256-row
 // workgroup tiles) for head dimension 128 (either input type) once the steady state dominates, i.e.
-// every resident workgroup of a domain gets at least one full-length tile of a head (two under the
-// causal mask, where a tile walks half the keys on average); 32 rows otherwise.  (Measured break-even:
-// +5 % and more from there on, a loss below.)
+// every resident workgroup of a domain gets at least one full-length tile of a head (nearly two under the
+// causal mask, where a tile walks half the keys on average), and only if the rounds of 32 tiles are well
+// filled: a last round with a few tiles costs this kernel a full round, while the 32-row kernel's workgroups
+// run faster when they have their compute unit to themselves.  Measured, 256-row tiles per head and XCD against
+// the gain over the 32-row kernel: plain 32: +9 %, 36: -10 %, 40: -9 %, 48: 0, 56: +11 %, 64: +9 %, 72: -5 %,
+// 80: +1 %, 88: +12 %, 96: +10 %; causal 48: -4 %, 56: +4 %, 64: +7 %, 72: +2 %, 88: +4 %, 96: +5 %.
 SAW_HD int default_rows_per_wavefront(int heads, int N, int d, bool causal, bool bf16) {
     (void)bf16;
     if (d != 128) return 32;
     const int parts = kDomains / gcd_i(heads, kDomains);
     const int wide_tiles = (N + 2 * kTileQ - 1) / (2 * kTileQ);
-    return (wide_tiles + parts - 1) / parts >= (causal ? 64 : 32) ? 64 : 32;
+    const int q = (wide_tiles + parts - 1) / parts;          // tiles of a head on one XCD
+    if (q < (causal ? 56 : 32)) return 32;
+    const int rounds = (q + 31) / 32;
+    // filled to at least 4/5 over all rounds (3/4 under the mask)
+    return (causal ? 4 * q >= 3 * 32 * rounds : 5 * q >= 4 * 32 * rounds) ? 64 : 32;
 }
 
 // Workgroups per domain that are resident together: 32 CUs per XCD x workgroups per CU.  A head

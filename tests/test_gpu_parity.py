@@ -380,7 +380,7 @@ def test_wide_rows_moving_maximum_and_default_choice(sa, oracle, causal, scale_f
     head), with score levels that jump from tile to tile by far more than the slack, so that the reference
     maximum is raised again and again in both scan directions.  Every row is compared with the oracle, at the
     usual scale (scores step by up to 53) and at eight times that (steps of several hundred)."""
-    H, N, d = 8, (256 * 128 if causal else 256 * 64) + 100, 128
+    H, N, d = 8, (256 * 128 if causal else 256 * 56) + 100, 128      # 129 (57) tiles of 256 rows: well-filled rounds
     scale = scale_factor / math.sqrt(d)
     assert sa.attn_fwd_launch_info(1, H, N, d, causal, dtype=dtype)["tile_q"] == 256
     g = torch.Generator("cpu").manual_seed(99)

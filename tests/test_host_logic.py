@@ -231,10 +231,15 @@ KERNEL_CHOICE = [
     ((4, 32, 32768, 128, True, "bf16"), (256, 32, 256, "persistent")),    # workload 5: 128 tiles of 256 rows per head
     ((1, 8, 256 * 31, 128, False, "f16"), (128, 62, 496, "persistent")),  # one tile short of the break-even
     ((1, 8, 256 * 32, 128, False, "f16"), (256, 32, 256, "persistent")),
-    ((1, 8, 256 * 63, 128, True, "f16"), (128, 64, 512, "persistent")),   # under the mask the break-even is twice as far out
+    ((1, 8, 256 * 55, 128, True, "f16"), (128, 64, 512, "persistent")),   # under the mask the break-even is nearly twice as
+    ((1, 8, 256 * 56, 128, True, "f16"), (256, 32, 256, "persistent")),   # far out
     ((1, 8, 256 * 64, 128, True, "f16"), (256, 32, 256, "persistent")),
+    ((1, 8, 256 * 65, 128, True, "f16"), (128, 64, 512, "persistent")),   # 65 of 96: a third round with one tile
+    ((1, 8, 256 * 36, 128, False, "f16"), (128, 64, 512, "persistent")),  # 36 of 64: a second round with four tiles
+    ((1, 8, 256 * 56, 128, False, "f16"), (256, 32, 256, "persistent")),  # 56 of 64
+    ((1, 8, 256 * 72, 128, False, "f16"), (128, 64, 512, "persistent")),  # 72 of 96
     ((1, 8, 256 * 70, 64, False, "f16"), (128, 96, 768, "persistent")),   # d = 64: three workgroups per CU
-    ((1, 8, 256 * 70, 128, False, "bf16"), (256, 32, 256, "persistent")),  # the element type plays no part
+    ((1, 8, 256 * 88, 128, False, "bf16"), (256, 32, 256, "persistent")),  # the element type plays no part
     ((1, 1, 256 * 8 * 32, 128, False, "f16"), (256, 32, 256, "persistent")),   # one head over 8 XCDs: 32 tiles each
     ((1, 1, 256 * 8 * 31, 128, False, "f16"), (128, 62, 496, "persistent")),
     ((2, 3, 333, 128, False, "f16"), (64, 6, 48, "grid")),          # 6 heads of 6 tiles of 64 rows (18 of 128: a small
