@@ -71,6 +71,10 @@ def parse():
     ap.add_argument("--align-rounds", action="store_true",
                     help="the workgroups of an XCD wait for each other after every round, not only between heads "
                          "(attn_fwd_variant; a study of how much the scan order can save at best)")
+    ap.add_argument("--qo-streaming", type=int, default=0, choices=[0, 1, 2, 3, 4],
+                    help="0: what attn_fwd does (3); 3: Q tiles in and O tiles out through LDS, whole lines, non-temporal; "
+                         "1: O only; 2: Q only; 4: neither (every lane loads and stores its own pieces, cached), "
+                         "through attn_fwd_variant: a study of what the tiles touched once cost the K/V tail in the L2")
     ap.add_argument("--evict", action="store_true",
                     help="overwrite a 1 GiB scratch buffer before every step so each launch starts cache-cold")
     return ap.parse_args()
@@ -188,8 +192,8 @@ def main():
         del src, dst
     info = sa.attn_fwd_launch_info(w.B, w.H, w.N, w.d, w.causal, dtype=w.dtype)
     var = sa.variant(rows_per_wavefront=args.rows_per_wavefront, align_rounds=int(args.align_rounds),
-                     kv_halves=args.kv_halves) \
-        if (args.rows_per_wavefront or args.align_rounds or args.kv_halves) else None
+                     kv_halves=args.kv_halves, qo_streaming=args.qo_streaming) \
+        if (args.rows_per_wavefront or args.align_rounds or args.kv_halves or args.qo_streaming) else None
     if var is not None:
         info = sa.attn_fwd_variant_launch_info(w.B, w.H, w.N, w.d, w.causal, var, w.dtype)
     ws, ws_bytes = None, 0

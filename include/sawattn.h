@@ -145,6 +145,12 @@ typedef struct sawattn_variant {
                                 the length of one wavefront's walk is the launch time;
                                 0 = default: 2 where it is supported and B*H*ceil(N/128) is at most 128 (d = 128),
                                 or, with d = 64 and N >= 2048, 384 (512 under the causal mask); else 1. */
+    int qo_streaming;        /* how the rows touched once per query tile pass the L2.  3: Q tiles are brought in and O tiles
+                                written out through LDS, whole 128-byte lines per instruction, marked non-temporal, so
+                                that at a round boundary they do not displace the K/V tail the sawtooth order
+                                (Sec. 3.4) is about to find in the L2; 1: O only; 2: Q only; 4: neither -- every lane
+                                loads and stores the 8- and 16-byte pieces of the rows it computes with, cached;
+                                0 = default (3).  Same values written in every mode. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round

@@ -37,7 +37,7 @@ class Variant(ctypes.Structure):
     """sawattn_variant: which launch / work decode to run (None everywhere = the default)."""
     _fields_ = [("launch", ctypes.c_int), ("decode", ctypes.c_int), ("slots_per_domain", ctypes.c_int),
                 ("tiles_per_workgroup", ctypes.c_int), ("rows_per_wavefront", ctypes.c_int),
-                ("align_rounds", ctypes.c_int), ("kv_halves", ctypes.c_int)]
+                ("align_rounds", ctypes.c_int), ("kv_halves", ctypes.c_int), ("qo_streaming", ctypes.c_int)]
 
 
 _LAUNCH_CODE = {"persistent": LAUNCH_PERSISTENT, "grid": LAUNCH_GRID, "auto": LAUNCH_AUTO}
@@ -45,10 +45,10 @@ _DECODE_CODE = {"domain": DECODE_DOMAIN, "linear": DECODE_LINEAR}
 
 
 def variant(launch="persistent", decode="domain", slots_per_domain=0, tiles_per_workgroup=0,
-            rows_per_wavefront=0, align_rounds=0, kv_halves=0) -> Variant:
+            rows_per_wavefront=0, align_rounds=0, kv_halves=0, qo_streaming=0) -> Variant:
     return Variant(_LAUNCH_CODE.get(launch, launch), _DECODE_CODE.get(decode, decode),
                    int(slots_per_domain), int(tiles_per_workgroup), int(rows_per_wavefront), int(align_rounds),
-                   int(kv_halves))
+                   int(kv_halves), int(qo_streaming))
 
 
 def _vptr(v):

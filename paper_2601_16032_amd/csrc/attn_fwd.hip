@@ -76,6 +76,8 @@ struct Params {
     int sawtooth;
     int negate_q;          // scale < 0: use -Q and |scale|
     int q_bf16;            // wide variant on converted inputs: Q is still bfloat16 (K and V are binary16 copies)
+    int stream_o;          // O leaves through LDS as whole lines, non-temporal (variant.qo_streaming)
+    int stream_q;          // Q arrives through LDS as whole lines, non-temporal
     int max_local;
     int ticket_set;        // which set of arrival counters this launch uses (domain_sync)
     float c;               // |scale| * log2(e): scores are handled in the log2 domain
@@ -180,6 +182,11 @@ struct LaneMap {
 // publishes the tile.
 __device__ __forceinline__ void load_to_lds_16B(const char* base, unsigned voff, unsigned lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
+}
+// The same marked non-temporal: data read once (a Q tile) that should not take the place of K/V tiles in the L2.
+__device__ __forceinline__ void load_to_lds_16B_nt(const char* base, unsigned voff, unsigned lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
                  :: "s"(lds_addr), "v"(voff), "s"(base) : "memory", "m0");
 }
 // The same with the LDS address given as a scalar base plus a compile-time offset (one scalar add into M0).
@@ -1217,6 +1224,29 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     __syncthreads();      // all reads of the last tile are done before anything refills the buffers
 }
 
+// The epilogue with variant.o_nontemporal: O leaves through LDS so that a store instruction writes whole 128-byte lines
+// (8 rows x 128 bytes per instruction, 16 bytes per lane), marked non-temporal: the rows of O are written once and never
+// read by the kernel, and written this way they do not take the place of K/V tiles in the L2.  (Non-temporal stores of
+// the 8- and 16-byte pieces a lane holds per row are not gathered into lines by the L2 and cost several times the
+// write traffic.)  `stage` is 4 KiB of LDS of this wavefront's own: 32 rows x 128 bytes, the 16-byte chunk c of row r at
+// chunk position c ^ (r & 7).  One call moves one 128-byte column block of the 32 rows; `mine` is the LDS byte offset
+// this lane writes its pieces to (row = lane & 31), rows_left the number of rows of the block inside the sequence.
+__device__ __forceinline__ void stage_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
+__device__ __forceinline__ void drain_stage(LDS_PTR(char) stage, char* dst, size_t row_bytes, int rows_left, int lane) {
+    stage_fence();
+    const int chunk = lane & 7;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = 8 * k + (lane >> 3);
+        const u4 x = *(LDS_PTR(u4))(stage + row * 128 + ((chunk ^ (row & 7)) << 4));
+        char* to = dst + row * row_bytes + chunk * 16;
+        // (the s_nop: a store of more than 8 bytes reads its data registers up to two cycles after issue, and the compiler
+        //  does not see a store in this statement when it decides what may overwrite them next)
+        if (row < rows_left) asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(to), "v"(x) : "memory");
+    }
+    stage_fence();
+}
+
 // One query tile (Alg. 1 body): rows [t*128*NH, (t+1)*128*NH) of head `hh`, K/V tiles j0, j0+step, ... (nkv of
 // them).  A wavefront owns NH halves of 32 query rows each (NH = 2: the wide variant).
 // HALVES (32 rows per wavefront): the tile has 64 rows; of its full, unmasked K/V tiles wavefronts
@@ -1245,6 +1275,32 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
     const int qrow = qw0 + ln;                // this lane's query row in half 0 (column of S^T)
 
     TileState<D> st[NH];
+    // With variant.qo_streaming the rows of Q come in the way K tiles do -- 64 rows at a time straight into LDS, whole
+    // lines per instruction, the four wavefronts together -- but marked non-temporal, and are read from there in the
+    // K operand's pattern, which is also Q's.  The buffers are free: the last range of the previous tile ended with a barrier.
+    unsigned q_at = 0;     // byte offset in LDS of this lane's first fragment of half 0
+    if (p.stream_q) {
+        int l2 = lane;
+        asm volatile("" : "+v"(l2));        // (a lane map of its own that does not live on: see the note on registers below)
+        const LaneMap<D> lq(wave, l2);
+        const unsigned lds0 = (unsigned)(size_t)lds;
+#pragma unroll
+        for (int m = 0; m < TQ / kTileKV; ++m) {
+            const int q0 = t * TQ + m * kTileKV;
+            const int first = q0 < N ? q0 : N - 1;          // rows beyond N repeat row N-1, as below
+            const char* base = Qh + (size_t)first * G::kRowBytes;
+#pragma unroll
+            for (int i = 0; i < G::kLoadsPerWave; ++i) {
+                const int row = lq.fill_src[i] / G::kRowBytes, chunk = lq.fill_src[i] % G::kRowBytes;
+                const int r = q0 + row < N ? q0 + row : N - 1;
+                load_to_lds_16B_nt(base, (unsigned)((r - first) * G::kRowBytes + chunk), lds0 + m * G::kTile + lq.fill_dst + i * 4096);
+            }
+        }
+        const int mine = HALVES ? wave & 1 : wave;           // which 32 * NH rows of the tile are this wavefront's
+        q_at = (mine * NH / 2) * G::kTile + ((mine * NH) & 1) * 32 * G::kRowBytes + lq.k_rd[0];
+        wait_tile_landed();
+        __syncthreads();
+    }
 #pragma unroll
     for (int h = 0; h < NH; ++h) {   // rows beyond N repeat row N-1 (computed, never stored)
         const int qr = qrow + 32 * h < N ? qrow + 32 * h : N - 1;
@@ -1252,7 +1308,9 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         const unsigned flip = p.negate_q ? 0x80008000u : 0u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            u4 v = *reinterpret_cast<const u4*>(qp + ks * 32);
+            // (chunk 2 ks + g of a row sits at chunk position (2 ks + g) ^ swz(row): k_rd[ks] = k_rd[0] ^ (32 ks))
+            u4 v = p.stream_q ? *(LDS_PTR(u4))(lds + ((q_at + h * 32 * G::kRowBytes) ^ (unsigned)(ks * 32)))
+                              : *reinterpret_cast<const u4*>(qp + ks * 32);
             v[0] ^= flip; v[1] ^= flip; v[2] ^= flip; v[3] ^= flip;
             if constexpr (NH == 2) {
                 if constexpr (!BF16) {
@@ -1270,6 +1328,7 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         st[h].M = -INFINITY;
         st[h].L = 0.f;
     }
+    if (p.stream_q) __syncthreads();      // the fragments are in registers before the first K/V fetch overwrites the rows
     const float c = p.c;
 
     // Tiles with index >= jm need the mask code: the ragged last tile, and under the causal mask
@@ -1337,7 +1396,6 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         if (step > 0)
             general_range<D, BF16, CAUSAL, true, NH>(st, lm, Kh, Vh, N, c, j0 + 2 * half * step, step, n_left, qw0, qrow, lane,
                                                      lds, run == 1);
-        if (run == 1) return;
     } else if (step > 0) {
         plain(j0);
         masked(j0 + n_plain * step);
@@ -1347,6 +1405,56 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
     }
 
     // ---- epilogue: O_i = acc / l  (the division Alg. 1 leaves implicit; Eq. 1 fixes it)
+    const bool writes = !HALVES || run == 0;     // of two wavefronts that share rows, the first holds the merged result
+    if (p.stream_o) {
+        wait_tile_landed();
+        __syncthreads();          // nothing is on its way into the K/V buffers any more: they serve as staging area
+        if (writes) {
+            LDS_PTR(char) stage = lds + wave * 4096;
+            const int sw = ln & 7;
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const float inv = 1.0f / pair_sum(st[h].L);
+                const int row0 = qw0 + 32 * h;
+                const int rows_left = N - row0;      // <= 0: the whole half lies beyond the sequence
+                if (p.o_dtype == SAWATTN_F32) {
+                    constexpr size_t RB = (size_t)D * 4;
+                    char* dst = static_cast<char*>(p.O) + ((size_t)hh * N + row0) * RB;
+#pragma unroll
+                    for (int db = 0; db < DB; ++db) {          // 32 columns = 128 bytes per row
+                        const f16v& o = st[h].o[db];
+#pragma unroll
+                        for (int rq = 0; rq < 4; ++rq) {
+                            const f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
+                            *(LDS_PTR(f4))(stage + ln * 128 + (((2 * rq + g) ^ sw) << 4)) = v;
+                        }
+                        drain_stage(stage, dst + db * 128, RB, rows_left, lane);
+                    }
+                } else {
+                    constexpr size_t RB = (size_t)D * 2;
+                    char* dst = static_cast<char*>(p.O) + ((size_t)hh * N + row0) * RB;
+#pragma unroll
+                    for (int pass = 0; pass < DB / 2; ++pass) {   // 64 columns = 128 bytes per row
+#pragma unroll
+                        for (int dbl = 0; dbl < 2; ++dbl) {
+                            const f16v& o = st[h].o[2 * pass + dbl];
+#pragma unroll
+                            for (int rq = 0; rq < 4; ++rq) {
+                                const f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
+                                LDS_PTR(char) at = stage + ln * 128 + (((4 * dbl + rq) ^ sw) << 4) + 8 * g;
+                                if (p.o_dtype == SAWATTN_F16) *(LDS_PTR(h4))at = __builtin_convertvector(v, h4);
+                                else *(LDS_PTR(b4))at = __builtin_convertvector(v, b4);
+                            }
+                        }
+                        drain_stage(stage, dst + pass * 128, RB, rows_left, lane);
+                    }
+                }
+            }
+        }
+        __syncthreads();          // the staging area is read before the next tile's fetches overwrite it
+        return;
+    }
+    if (!writes) return;
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
         const float inv = 1.0f / pair_sum(st[h].L);
@@ -1559,6 +1667,8 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
         decode = v->decode == SAWATTN_DECODE_LINEAR ? kDecodeLinear : kDecodeDomain;
         max_slots = v->slots_per_domain;
         if (v->tiles_per_workgroup) tiles_per_wg = v->tiles_per_workgroup;
+        if (v->qo_streaming < 0 || v->qo_streaming > 4)
+            return fail(SAWATTN_ERR_INVALID_ARG, "variant.qo_streaming must be 0 (default), 1 (O), 2 (Q), 3 (both) or 4 (neither)");
         if (v->align_rounds != 0 && v->align_rounds != 1)
             return fail(SAWATTN_ERR_INVALID_ARG, "variant.align_rounds must be 0 or 1");
         align_rounds = v->align_rounds == 1;
@@ -1646,6 +1756,11 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.sawtooth = scan_order == SAWATTN_SCAN_SAWTOOTH;
     p.negate_q = scale < 0.f;
     p.q_bf16 = converted;
+    {
+        const int streaming = variant && variant->qo_streaming ? variant->qo_streaming : 3;
+        p.stream_o = streaming == 1 || streaming == 3;
+        p.stream_q = streaming == 2 || streaming == 3;
+    }
     // Never zero: the kernels mask a key by giving it the score -inf and rely on -inf * c = -inf.  At this floor
     // every finite score times c is below 2^-60 in magnitude, so scale = 0 still gives exp2(0) = 1 for every visible key.
     p.c = std::fmax((float)(std::fabs((double)scale) * 1.4426950408889634074), 1e-30f);
@@ -1836,7 +1951,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in
 }
 
 const char* attn_last_error(void) { return sawattn::g_err; }
-int attn_version(void) { return 210; }
+int attn_version(void) { return 211; }
 const char* sawattn_last_error(void) { return attn_last_error(); }
 int sawattn_version(void) { return attn_version(); }
 

@@ -387,7 +387,8 @@ def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, 
 def test_variant_fields_are_validated(sa):
     vli = sa.attn_fwd_variant_launch_info
     for bad in (dict(launch=3), dict(launch=-1), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
-                dict(tiles_per_workgroup=3), dict(align_rounds=2), dict(align_rounds=-1)):
+                dict(tiles_per_workgroup=3), dict(align_rounds=2), dict(align_rounds=-1), dict(qo_streaming=5),
+                dict(qo_streaming=-1)):
         with pytest.raises(binding.SawattnError) as e:
             vli(1, 8, 2048, 128, False, sa.variant(**bad))
         assert e.value.code == binding.ERR_INVALID_ARG and "variant." in str(e.value)
