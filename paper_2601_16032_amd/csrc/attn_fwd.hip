@@ -1301,10 +1301,12 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         wait_tile_landed();
         __syncthreads();
     }
+    int lane_q = lane;
+    asm volatile("" : "+v"(lane_q));      // (addresses used once: built from a copy of the lane index of their own)
 #pragma unroll
     for (int h = 0; h < NH; ++h) {   // rows beyond N repeat row N-1 (computed, never stored)
-        const int qr = qrow + 32 * h < N ? qrow + 32 * h : N - 1;
-        const char* qp = Qh + (size_t)qr * G::kRowBytes + g * 16;
+        const int qr = qw0 + (lane_q & 31) + 32 * h < N ? qw0 + (lane_q & 31) + 32 * h : N - 1;
+        const char* qp = Qh + (size_t)qr * G::kRowBytes + (lane_q >> 5) * 16;
         const unsigned flip = p.negate_q ? 0x80008000u : 0u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -1406,11 +1408,15 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
 
     // ---- epilogue: O_i = acc / l  (the division Alg. 1 leaves implicit; Eq. 1 fixes it)
     const bool writes = !HALVES || run == 0;     // of two wavefronts that share rows, the first holds the merged result
+    const int lane_in = lane;
     if (p.stream_o) {
         wait_tile_landed();
         __syncthreads();          // nothing is on its way into the K/V buffers any more: they serve as staging area
         if (writes) {
             LDS_PTR(char) stage = lds + wave * 4096;
+            int lane = lane_in;
+            asm volatile("" : "+v"(lane));     // lane-derived addresses are built here, not carried across the scan
+            const int g = lane >> 5, ln = lane & 31;
             const int sw = ln & 7;
 #pragma unroll
             for (int h = 0; h < NH; ++h) {
@@ -1455,18 +1461,21 @@ __device__ __forceinline__ void process_q_tile(const Params& p, const LaneMap<D>
         return;
     }
     if (!writes) return;
+    int lane_out = lane_in;
+    asm volatile("" : "+v"(lane_out));
+    const int g_out = lane_out >> 5, qrow_out = qw0 + (lane_out & 31);
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
         const float inv = 1.0f / pair_sum(st[h].L);
-        if (qrow + 32 * h < N) {
-            const size_t orow = ((size_t)hh * N + qrow + 32 * h) * D;
+        if (qrow_out + 32 * h < N) {
+            const size_t orow = ((size_t)hh * N + qrow_out + 32 * h) * D;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int rq = 0; rq < 4; ++rq) {
                     const f16v& o = st[h].o[db];
                     f4 v = {o[4 * rq] * inv, o[4 * rq + 1] * inv, o[4 * rq + 2] * inv, o[4 * rq + 3] * inv};
-                    const size_t col = 32 * db + 8 * rq + 4 * g;
+                    const size_t col = 32 * db + 8 * rq + 4 * g_out;
                     if (p.o_dtype == SAWATTN_F32) {
                         *reinterpret_cast<f4*>(static_cast<float*>(p.O) + orow + col) = v;
                     } else if (p.o_dtype == SAWATTN_F16) {

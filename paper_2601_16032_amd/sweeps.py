@@ -12,7 +12,8 @@ Studies
   seqlen    Sec. 3.2 / 3.3: sequence length 2K...128K at B=1, H in {1, 8}, d in {64, 128}:
             L2 requests against 2NdE(1 + N/T_q) (T_q = 128, or 256 where the library picks its wide
             variant), and where non-compulsory misses set in.
-  resident  Sec. 3.4: G = 8 w persistent workgroups, w = 1...64 (96 at d = 64) per XCD: hit rate against 1 - 1/w.
+  resident  Sec. 3.4: G = 8 w persistent workgroups, w = 1...64 (96 at d = 64) per XCD: hit rate against 1 - 1/w;
+            the sawtooth points a second time with qo_streaming = 4 (Q and O tiles as ordinary cached traffic).
   decode    Sec. 2.2 Alg. 2 as printed (one linear stride over all XCDs) against the per-XCD decode.
   launch    Alg. 3 (direct launch, one or two query tiles per workgroup) against the persistent
             launch, both scan orders (Sec. 4.3's two program variants).
@@ -57,6 +58,8 @@ def study_points(study: str):
             for w in (1, 2, 4, 8, 16, 32, 64) + ((96,) if d == 64 else ()):
                 for order in ("cyclic", "sawtooth"):
                     pts.append(_pt(1, H, N, d, order=order, slots_per_domain=w))
+                # the same turn-around with Q and O tiles passing the L2 as ordinary cached traffic
+                pts.append(_pt(1, H, N, d, order="sawtooth", slots_per_domain=w, qo_streaming=4))
     elif study == "decode":
         for (B, H, N, d, causal) in ((1, 32, 16384, 128, False), (1, 16, 32768, 128, True), (8, 1, 32768, 64, False)):
             for decode in ("domain", "linear"):
