@@ -72,7 +72,7 @@ def parse():
                     help="the workgroups of an XCD wait for each other after every round, not only between heads "
                          "(attn_fwd_variant; a study of how much the scan order can save at best)")
     ap.add_argument("--qo-streaming", type=int, default=0, choices=[0, 1, 2, 3, 4],
-                    help="0: what attn_fwd does (3); 3: Q tiles in and O tiles out through LDS, whole lines, non-temporal; "
+                    help="0: what attn_fwd does (3 on these workloads but the first two, where it is 1); 3: Q tiles in and O tiles out through LDS, whole lines, non-temporal; "
                          "1: O only; 2: Q only; 4: neither (every lane loads and stores its own pieces, cached), "
                          "through attn_fwd_variant: a study of what the tiles touched once cost the K/V tail in the L2")
     ap.add_argument("--evict", action="store_true",

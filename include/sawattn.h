@@ -150,7 +150,8 @@ typedef struct sawattn_variant {
                                 that at a round boundary they do not displace the K/V tail the sawtooth order
                                 (Sec. 3.4) is about to find in the L2; 1: O only; 2: Q only; 4: neither -- every lane
                                 loads and stores the 8- and 16-byte pieces of the rows it computes with, cached;
-                                0 = default (3).  Same values written in every mode. */
+                                0 = default: 3 where K and V of a head take at least 2 MiB (half the L2 of an XCD),
+                                else 1.  Same values written in every mode. */
 } sawattn_variant;
 /*
  * Scan direction per variant with SAWATTN_SCAN_SAWTOOTH: persistent + domain decode: parity of the round

@@ -1766,7 +1766,10 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.negate_q = scale < 0.f;
     p.q_bf16 = converted;
     {
-        const int streaming = variant && variant->qo_streaming ? variant->qo_streaming : 3;
+        // Default: O always; Q where a head's K and V are at least half an L2 (4 MiB per XCD) -- below that no scan
+        // order has anything to lose to the Q tiles, and direct loads hide their latency behind the first K/V fetch.
+        const bool long_heads = (unsigned long long)N * d * 4u >= (2u << 20);
+        const int streaming = variant && variant->qo_streaming ? variant->qo_streaming : (long_heads ? 3 : 1);
         p.stream_o = streaming == 1 || streaming == 3;
         p.stream_q = streaming == 2 || streaming == 3;
     }
