@@ -191,6 +191,7 @@ typedef struct sawattn_launch_info {
     int max_local_tiles;   /* most query tiles any one workgroup processes */
     int launch;            /* SAWATTN_LAUNCH_PERSISTENT or SAWATTN_LAUNCH_GRID: which of the two runs */
     int tiles_per_workgroup; /* grid launch: consecutive query tiles per workgroup (1 with the persistent launch) */
+    int qo_streaming;        /* 1, 2, 3 or 4 as in sawattn_variant: how Q and O tiles pass the L2 in this launch */
 } sawattn_launch_info;
 
 /*

@@ -27,7 +27,8 @@ _SCAN_CODE = {"cyclic": SCAN_CYCLIC, "sawtooth": SCAN_SAWTOOTH, SCAN_CYCLIC: SCA
 class LaunchInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int) for n in (
         "tile_q", "tile_kv", "block_threads", "grid", "lds_bytes", "domains", "slots",
-        "parts_per_head", "q_tiles_per_head", "max_local_tiles", "launch", "tiles_per_workgroup")]
+        "parts_per_head", "q_tiles_per_head", "max_local_tiles", "launch", "tiles_per_workgroup",
+        "qo_streaming")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

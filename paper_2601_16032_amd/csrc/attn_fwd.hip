@@ -1602,6 +1602,7 @@ void fill_info(const Schedule& s, int d, sawattn_launch_info* out) {
     out->max_local_tiles = s.local_iters;
     out->launch = s.launch == kLaunchGrid ? SAWATTN_LAUNCH_GRID : SAWATTN_LAUNCH_PERSISTENT;
     out->tiles_per_workgroup = s.tiles_per_wg;
+    out->qo_streaming = s.qo_streaming;
 }
 
 std::atomic<unsigned> g_ticket_turn{0};
@@ -1694,6 +1695,7 @@ int schedule_for(int B, int H, int N, int d, bool causal, bool bf16, const sawat
     if (tiles_per_wg == 0) tiles_per_wg = 2;
     if (max_slots == 0) max_slots = resident_slots(d, tile_q);
     *out = make_schedule(B * H, N, causal, launch, decode, max_slots, tiles_per_wg, tile_q, align_rounds);
+    out->qo_streaming = v && v->qo_streaming ? v->qo_streaming : default_qo_streaming(N, d);
     return SAWATTN_OK;
 }
 
@@ -1766,12 +1768,8 @@ int run(const void* Q, const void* K, const void* V, void* O, int B, int H, int 
     p.negate_q = scale < 0.f;
     p.q_bf16 = converted;
     {
-        // Default: O always; Q where a head's K and V are at least half an L2 (4 MiB per XCD) -- below that no scan
-        // order has anything to lose to the Q tiles, and direct loads hide their latency behind the first K/V fetch.
-        const bool long_heads = (unsigned long long)N * d * 4u >= (2u << 20);
-        const int streaming = variant && variant->qo_streaming ? variant->qo_streaming : (long_heads ? 3 : 1);
-        p.stream_o = streaming == 1 || streaming == 3;
-        p.stream_q = streaming == 2 || streaming == 3;
+        p.stream_o = sched.qo_streaming == 1 || sched.qo_streaming == 3;
+        p.stream_q = sched.qo_streaming == 2 || sched.qo_streaming == 3;
     }
     // Never zero: the kernels mask a key by giving it the score -inf and rely on -inf * c = -inf.  At this floor
     // every finite score times c is below 2^-60 in magnitude, so scale = 0 still gives exp2(0) = 1 for every visible key.
@@ -1963,7 +1961,7 @@ int attn_fwd_plan(int B, int H, int N, int d, int causal, int scan_order, int in
 }
 
 const char* attn_last_error(void) { return sawattn::g_err; }
-int attn_version(void) { return 211; }
+int attn_version(void) { return 212; }
 const char* sawattn_last_error(void) { return attn_last_error(); }
 int sawattn_version(void) { return attn_version(); }
 

@@ -95,6 +95,13 @@ SAW_HD int default_kv_halves(int heads, int N, int d, bool causal, bool bf16) {
 // walked backward (the step-2 alternation of Sec. 4.3).
 enum { kLaunchPersistent = 0, kLaunchGrid = 1 };
 
+// How the tiles touched once per query tile pass the L2 when the caller leaves it open: O always as whole non-temporal
+// lines; Q as well where K and V of a head take at least half the 4 MiB L2 of an XCD -- below that no scan order has
+// anything to lose to the Q tiles, and direct loads hide their latency behind the first K/V fetch.
+SAW_HD int default_qo_streaming(int N, int d) {
+    return (unsigned long long)N * (unsigned)d * 4u >= (2u << 20) ? 3 : 1;
+}
+
 // Launch when the caller leaves the choice open.  The persistent hand-out gives one head at a time to the
 // workgroups of an XCD, which is what keeps a long head's K/V in one L2; a head with fewer query tiles than the
 // XCD holds workgroups then leaves compute units idle, and with several such heads per XCD one after the other
@@ -134,6 +141,7 @@ struct Schedule {
     int local_iters;        // local iterations every workgroup runs through (some may be idle)
     int sync_heads;         // persistent, domain decode: the workgroups of a domain wait for each other between heads
     int sync_rounds;        // ... and after every round as well (a study of Sec. 3.4's lockstep; costs time)
+    int qo_streaming;       // 1: O tiles leave through LDS as whole non-temporal lines; 2: Q tiles arrive that way; 3: both; 4: neither
 };
 
 struct Work {
@@ -149,6 +157,7 @@ SAW_HD Schedule make_schedule(int heads, int N, bool causal, int launch, int dec
                               int tile_q = kTileQ, bool align_rounds = false) {
     Schedule s;
     s.heads = heads;
+    s.qo_streaming = 0;     // the caller's choice: not part of who computes what
     s.tile_q = tile_q;
     s.q_tiles = (N + tile_q - 1) / tile_q;
     s.kv_tiles = (N + kTileKV - 1) / kTileKV;

@@ -384,6 +384,20 @@ def test_host_plan_with_rows_per_wavefront_matches_schedule_oracle(sa, B, H, N, 
     assert seen == {(h, t) for h in range(B * H) for t in range(geo["q_tiles"])}
 
 
+@pytest.mark.parametrize("N,d,want", [
+    (256, 64, 1), (2048, 64, 1), (8191, 64, 1), (8192, 64, 3), (32768, 64, 3),      # K+V of a head: N * d * 4 bytes
+    (512, 128, 1), (4095, 128, 1), (4096, 128, 3), (8192, 128, 3), (16384, 128, 3),
+])
+def test_q_tiles_are_streamed_only_past_half_an_l2(sa, N, d, want):
+    """What attn_fwd does with the tiles touched once, cases listed by hand: O always through LDS as whole
+    non-temporal lines (1), Q as well (3) from 2 MiB of K+V per head on; a variant's choice is reported as given."""
+    for causal in (False, True):
+        assert sa.attn_fwd_launch_info(1, 8, N, d, causal, "sawtooth", "f16")["qo_streaming"] == want
+        assert sa.attn_fwd_variant_launch_info(2, 3, N, d, causal, sa.variant(), "bf16")["qo_streaming"] == want
+        for mode in (1, 2, 3, 4):
+            assert sa.attn_fwd_variant_launch_info(1, 8, N, d, causal, sa.variant(qo_streaming=mode))["qo_streaming"] == mode
+
+
 def test_variant_fields_are_validated(sa):
     vli = sa.attn_fwd_variant_launch_info
     for bad in (dict(launch=3), dict(launch=-1), dict(decode=-1), dict(slots_per_domain=65), dict(slots_per_domain=-1),
