@@ -712,3 +712,42 @@ def test_random_shapes_through_the_plain_entry_point(sa, oracle, seed):
             got = run_gpu(sa, Q, K, V, scale, causal, order, o_dtype=torch.float32)
             assert_close(got, want, f"random case {seed}/{case}: {B},{H},{N},{d} {dtype} causal={causal} {order} {info}")
     assert len(kinds) >= 3, kinds      # the draw reached several kinds of launch
+
+
+# ------------------------------------------------------------------ the entry point that allocates nothing, replayed from a HIP graph
+@pytest.mark.parametrize("B,H,N,d,dtype,causal", [
+    (1, 16, 4096, 128, "f16", True),       # persistent launch, two heads per XCD: the workgroups of an XCD wait between heads
+    (1, 8, 2048, 64, "f16", False),        # 64-row tiles, the two halves of the scan at once
+    (1, 8, 8192, 128, "bf16", False),      # binary16 copies of K and V in the library's fixed scratch array, wide kernel
+])
+def test_static_entry_point_replays_from_a_graph(sa, oracle, B, H, N, d, dtype, causal):
+    """attn_fwd_static is for callers that cannot allocate, graph capture among them: captured once and replayed four
+    times, with eager launches of other problems and synchronisations in between and new input values before every
+    replay, every replay equals the eager call on the same values bit for bit, and the first one the oracle."""
+    scale = 1.0 / math.sqrt(d)
+    Q, K, V = (t.cuda() for t in workloads.make_random(B, H, N, d, dtype, seed=900 + d))
+    O = torch.empty(B, H, N, d, device="cuda", dtype=torch.float32)
+    other = [t.cuda() for t in workloads.make_random(2, 3, 700, d, dtype, seed=5)]
+    sa.attn_fwd_static(Q, K, V, O, scale=scale, causal=causal, scan_order="sawtooth")      # set-up happens here, not under capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sa.attn_fwd_static(Q, K, V, O, scale=scale, causal=causal, scan_order="sawtooth")
+    torch.cuda.synchronize()
+    for rep in range(4):
+        fresh = [t.cuda() for t in workloads.make_random(B, H, N, d, dtype, seed=910 + rep)]
+        for dst, src in zip((Q, K, V), fresh):
+            dst.copy_(src)
+        O.fill_(float("nan"))
+        sa.attn_fwd(*other, scale=scale, causal=not causal, scan_order="cyclic")            # the program's own eager work
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = O.clone()
+        want = sa.attn_fwd_static(Q, K, V, scale=scale, causal=causal, scan_order="sawtooth", o_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep}: max diff {(got - want).abs().max().item():.3e}"
+        if rep == 0:
+            rows = list(range(0, N, 97)) + [N - 1]
+            ref = oracle.attention(fresh[0].cpu(), fresh[1].cpu(), fresh[2].cpu(), scale, causal=causal, rows=rows)
+            assert_close(got.double().cpu().numpy()[:, :, rows], ref, f"graph replay {B},{H},{N},{d} {dtype}")
