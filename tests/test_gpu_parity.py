@@ -626,12 +626,17 @@ def test_halved_scan_is_what_the_small_workloads_run(sa):
     (1, 2, 8192 + 100, 128, "bf16", True, torch.bfloat16, dict(rows_per_wavefront=64)),
     (2, 40, 3000, 64, "f16", True, torch.float16, dict()),
     (1, 24, 1111, 128, "bf16", False, torch.float32, dict(launch="grid", tiles_per_workgroup=2)),
+    (2, 2, 1, 64, "f16", False, torch.float32, dict()),                 # a single row: every row of the Q tile repeats it
+    (1, 3, 37, 128, "bf16", True, torch.float32, dict()),
+    (1, 2, 65, 64, "f16", True, torch.float16, dict(kv_halves=1)),      # second 64-row Q tile holds one row
+    (1, 2, 300, 128, "f16", False, torch.float32, dict(rows_per_wavefront=64)),   # 256-row tile, last wavefront's rows all beyond N
 ])
 def test_streamed_q_and_o_tiles_carry_the_same_values(sa, oracle, B, H, N, d, dtype, causal, o_dtype, kw):
     """variant.qo_streaming changes the way Q tiles come in and O tiles go out (through LDS, whole lines, non-temporal)
     and nothing of what is computed: every mode bit for bit against mode 4, where each lane loads and stores its own
     pieces, in every output type and kernel shape, with ragged last tiles and several tiles per workgroup, a negative
-    scale (Q's sign is flipped on the way in); and the default against the oracle on sampled rows where O is fp32."""
+    scale (Q's sign is flipped on the way in), sequences shorter than a tile; and mode 3 against the oracle on sampled
+    rows where O is fp32."""
     Q, K, V = workloads.make_random(B, H, N, d, dtype, seed=77)
     scale = (-1.0 if N == 777 else 1.0) / math.sqrt(d)
     Qg, Kg, Vg = Q.cuda(), K.cuda(), V.cuda()
@@ -645,9 +650,9 @@ def test_streamed_q_and_o_tiles_carry_the_same_values(sa, oracle, B, H, N, d, dt
     for mode in (1, 2, 3, 0):
         assert torch.equal(outs[4].view(torch.uint8), outs[mode].view(torch.uint8)), f"qo_streaming={mode}"
     if o_dtype == torch.float32:
-        rows = list(range(0, N, 53)) + [N - 1]
+        rows = sorted(set(list(range(0, N, 53)) + [N - 1]))
         want = oracle.attention(Q, K, V, scale, causal=causal, rows=rows)
-        assert_close(outs[0].double().numpy()[:, :, rows], want, f"streamed Q and O {N},{d} {dtype}")
+        assert_close(outs[3].double().numpy()[:, :, rows], want, f"streamed Q and O {N},{d} {dtype}")
 
 
 # ------------------------------------------------------------------ short heads, several per XCD: attn_fwd launches one workgroup per tile
