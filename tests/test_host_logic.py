@@ -521,3 +521,31 @@ def test_build_refuses_wide_kernels_that_spill():
         hip_build.check_wide_kernels(hip_build.kernel_resources(remarks(188)))
     with pytest.raises(RuntimeError, match="expected the resource usage of 4"):
         hip_build.check_wide_kernels({})
+
+
+def test_header_is_plain_c_and_the_binding_mirrors_its_structs(tmp_path):
+    """include/sawattn.h compiles as C99 on its own, and the ctypes mirrors in binding.py have the header's field
+    names, order, offsets and sizes (read back from a program gcc builds from the header)."""
+    import ctypes
+    import re
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = open(os.path.join(root, "include", "sawattn.h")).read()
+    fields = {}
+    for name in ("sawattn_variant", "sawattn_launch_info"):
+        body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (name, name), header, re.S).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        fields[name] = re.findall(r"\bint\s+(\w+)\s*;", body)
+    prints = "".join('printf("%s.%s %%zu\\n", offsetof(%s, %s));\n' % (s, f, s, f) for s, fs in fields.items() for f in fs)
+    prints += "".join('printf("%s %%zu\\n", sizeof(%s));\n' % (s, s) for s in fields)
+    src = tmp_path / "abi.c"
+    src.write_text('#include <stddef.h>\n#include <stdio.h>\n#include "sawattn.h"\nint main(void) {\n' + prints + "return 0; }\n")
+    exe = tmp_path / "abi"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src), "-o", str(exe)],
+                   check=True, capture_output=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, mirror in (("sawattn_variant", binding.Variant), ("sawattn_launch_info", binding.LaunchInfo)):
+        assert [n for n, _ in mirror._fields_] == fields[cname]
+        assert int(got[cname]) == ctypes.sizeof(mirror)
+        for n, _ in mirror._fields_:
+            assert int(got[f"{cname}.{n}"]) == getattr(mirror, n).offset
