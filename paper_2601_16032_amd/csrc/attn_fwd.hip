@@ -1224,13 +1224,14 @@ __device__ __forceinline__ void pipelined_range_wide(TileState<128> (&st)[2], co
     __syncthreads();      // all reads of the last tile are done before anything refills the buffers
 }
 
-// The epilogue with variant.o_nontemporal: O leaves through LDS so that a store instruction writes whole 128-byte lines
-// (8 rows x 128 bytes per instruction, 16 bytes per lane), marked non-temporal: the rows of O are written once and never
-// read by the kernel, and written this way they do not take the place of K/V tiles in the L2.  (Non-temporal stores of
-// the 8- and 16-byte pieces a lane holds per row are not gathered into lines by the L2 and cost several times the
-// write traffic.)  `stage` is 4 KiB of LDS of this wavefront's own: 32 rows x 128 bytes, the 16-byte chunk c of row r at
-// chunk position c ^ (r & 7).  One call moves one 128-byte column block of the 32 rows; `mine` is the LDS byte offset
-// this lane writes its pieces to (row = lane & 31), rows_left the number of rows of the block inside the sequence.
+// The epilogue where variant.qo_streaming asks for it: O leaves through LDS so that a store instruction writes whole
+// 128-byte lines (8 rows x 128 bytes per instruction, 16 bytes per lane), marked non-temporal: the rows of O are written
+// once and never read by the kernel, and written this way they do not take the place of K/V tiles in the L2.
+// (Non-temporal stores of the 8- and 16-byte pieces a lane holds per row are not gathered into lines by the L2 and cost
+// several times the write traffic.)  `stage` is 4 KiB of LDS of this wavefront's own: 32 rows x 128 bytes, the 16-byte
+// chunk c of row r at chunk position c ^ (r & 7), filled by the caller with one 128-byte column block of its 32 rows.
+// drain_stage() writes that block out: `dst` points at the block's first row in O, row_bytes is O's row pitch,
+// rows_left the number of the 32 rows that lie inside the sequence (<= 0: none).
 __device__ __forceinline__ void stage_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 __device__ __forceinline__ void drain_stage(LDS_PTR(char) stage, char* dst, size_t row_bytes, int rows_left, int lane) {
     stage_fence();
