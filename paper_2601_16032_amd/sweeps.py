@@ -1,8 +1,8 @@
 """The paper's cache studies as sweeps over the attention kernel (one GPU).
 
 Each study is a list of points (shape, launch variant, scan order).  A point is run as
-`--warmup` untimed plus `--launches` timed launches of the HIP kernel through the C ABI, timed with
-events on the launch stream, and printed as one JSON line together with what the traffic model
+`--warmup` untimed plus `--launches` timed launches of the HIP kernel through the C ABI (after `--settle-ms`
+of untimed launches where the times are what the run is for), timed with events on the launch stream, and printed as one JSON line together with what the traffic model
 (Sec. 3.2-3.4, Sec. 4) predicts for it.  Run the same command under `rocprofv3 --pmc ...
 --kernel-trace` to get the L2 counters of every launch: the attention dispatches appear in the
 order of the points, `warmup + launches` per point, which the `dispatches` field of each line
@@ -32,6 +32,7 @@ import argparse
 import json
 import math
 import sys
+import time
 
 from . import traffic_model as tm
 from . import workloads
@@ -116,6 +117,9 @@ def main(argv=None):
     ap.add_argument("--points", default="", help="comma-separated point indices or a:b ranges (default: all)")
     ap.add_argument("--launches", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--settle-ms", type=float, default=0.0,
+                    help="untimed launches of a point for this long before its warm-up, so that the clock has settled "
+                         "(for runs that are timed; leave at 0 under the profiler)")
     ap.add_argument("--list", action="store_true", help="print the points and exit (needs no GPU)")
     args = ap.parse_args(argv)
 
@@ -158,17 +162,37 @@ def main(argv=None):
         def launch():
             sa.attn_fwd_variant(Q, K, V, O, scale=scale, causal=pt["causal"], scan_order=pt["order"], variant=var)
 
+        settle = 0
+        if args.settle_ms > 0:
+            t0 = time.perf_counter()
+            while (time.perf_counter() - t0) * 1e3 < args.settle_ms:
+                launch()
+                settle += 1
+                if settle % 8 == 0:
+                    torch.cuda.synchronize()
         for _ in range(args.warmup):
             launch()
+        # A timed sample is `reps` launches back to back: 1 under the profiler, in a timed run as many as fill about
+        # 0.3 ms, so that the host's own time per launch does not show in short kernels.
+        reps = 1
+        if args.settle_ms > 0:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            launch()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            settle += 1
+            reps = max(1, min(64, int(0.3 / max(e0.elapsed_time(e1), 1e-3)) + 1))
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.launches + 1)]
         ev[0].record(stream)
         for k in range(args.launches):
-            launch()
+            for _ in range(reps):
+                launch()
             ev[k + 1].record(stream)
         torch.cuda.synchronize()
-        ms = sorted(ev[k].elapsed_time(ev[k + 1]) for k in range(args.launches))
+        ms = sorted(ev[k].elapsed_time(ev[k + 1]) / reps for k in range(args.launches))
         flops = 4.0 * pt["B"] * pt["H"] * pt["N"] ** 2 * pt["d"] * (0.5 if pt["causal"] else 1.0)
-        n = args.warmup + args.launches
+        n = settle + args.warmup + args.launches * reps
         print(json.dumps({"study": args.study, "point": i, **pt, "grid": info["grid"], "slots": info["slots"],
                           "tile_q": info["tile_q"], "launch": ("persistent", "grid")[info["launch"]],
                           "parts_per_head": info["parts_per_head"], "ms_median": ms[len(ms) // 2], "ms_min": ms[0],
