@@ -256,7 +256,7 @@ def main():
                      "traffic": traffic.get(head), "traffic_source": profile,
                      "kernel_ms": r["kernel_ms"], "kernel": kernel},
         "scan_orders": {o: {"tflops": res[o]["tflops"], "kernel_ms": res[o]["kernel_ms"],
-                            "tcc_miss_profiled": misses.get(o)} for o in orders},
+                            "tcc_miss_profiled": misses.get(o), "hbm_bytes_profiled": traffic.get(o)} for o in orders},
         "counters_from": profile,
     }
     if not args.no_mfma_probe:
